@@ -1,0 +1,180 @@
+/*
+ * spiral.h — C ABI of the MI355X (gfx950) self-play decode library.
+ *
+ * The library implements the computation that dominates SPIRAL's run time: the
+ * batched autoregressive generation y ~ pi_theta(. | s) of every game turn
+ * (Sec. 3 "Self-play"; Alg. 1, generation step) with the actor's sampling
+ * settings (hyper-parameter table, App. D: temperature 1.0, top-p 1.0, top-k -1,
+ * i.e. an untruncated categorical), plus the role-conditioned advantage
+ * estimation baseline (Sec. 3, RAE equation; Alg. 1, policy-optimisation loop).
+ *
+ * General rules
+ *  - Every function returns SPIRAL_OK (0) or a negative SPIRAL_ERR_* code; it
+ *    never throws and never aborts.  spiral_last_error() returns a thread-local
+ *    description of the last failure on the calling thread.
+ *  - "dev" pointers are HIP device pointers, "host" pointers are ordinary host
+ *    memory.  The caller owns ALL device memory (weights, KV pool, workspace,
+ *    logits, token buffers) and the stream.  The library never allocates or
+ *    frees device memory and never synchronises the stream; all device work is
+ *    enqueued on the stream that is passed in (`stream` is a hipStream_t, NULL =
+ *    the default stream).  Host arrays are consumed before the call returns.
+ *  - Opaque host objects (model, pool, RAE state) are created and freed by the
+ *    library.  Calls on the same object must not overlap.
+ *  - A failed call leaves sequence lengths and page tables unchanged.
+ */
+#ifndef SPIRAL_H
+#define SPIRAL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPIRAL_OK               0
+#define SPIRAL_ERR_INVALID_ARG (-1)  /* null pointer, bad id, duplicate sequence, misaligned buffer */
+#define SPIRAL_ERR_SHAPE       (-2)  /* geometry or size the kernels do not support */
+#define SPIRAL_ERR_OOM_KV      (-3)  /* not enough free KV pages / block-table slots / workspace */
+#define SPIRAL_ERR_NOT_LOADED  (-4)  /* object handle is null or already freed */
+#define SPIRAL_ERR_HIP         (-5)  /* a HIP runtime call failed (text in spiral_last_error) */
+
+#define SPIRAL_WEIGHT_FP32 0
+#define SPIRAL_WEIGHT_BF16 1
+
+#define SPIRAL_MAX_BATCH 1024        /* sequences per prefill / decode / sample call */
+
+/* Decoder geometry.  The paper names its policies only by model family (Sec. 4,
+ * "Models"); the block is the standard pre-norm decoder of those families:
+ * RMSNorm -> QKV (+bias | per-head q/k RMSNorm) -> RoPE (rotate-half) -> causal
+ * GQA attention -> output projection + residual -> RMSNorm -> SwiGLU MLP +
+ * residual; final RMSNorm and LM head. */
+typedef struct spiral_model_config {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, ffn_dim, vocab;
+    float   rope_theta;      /* RoPE base; pair (j, j+head_dim/2) turns by pos * theta^(-2j/head_dim) */
+    float   rms_eps;         /* added to the mean square inside the square root */
+    int32_t qk_norm;         /* 1: RMSNorm over head_dim of every q and k head (gain shared by heads), before RoPE */
+    int32_t qkv_bias;        /* 1: bias on the q, k, v projections, added before RoPE */
+    int32_t tie_lm_head;     /* informational: lm_head pointer aliases the embedding */
+    int32_t weight_dtype;    /* SPIRAL_WEIGHT_FP32 or SPIRAL_WEIGHT_BF16 (matrices, embedding, biases) */
+    int32_t kv_block_tokens; /* tokens per KV page; must be 16 */
+} spiral_model_config;
+
+/* Order of the device weight pointer table handed to spiral_model_load:
+ *   [0] embedding [vocab, d_model]   [1] final RMSNorm gain [d_model] (fp32)   [2] lm_head [vocab, d_model]
+ *   then, for layer l, 14 slots starting at 3 + 14*l, in the order below.  Matrices are row-major
+ *   [out_features, in_features] in weight_dtype; biases in weight_dtype; all gains are fp32.
+ *   Slots a geometry does not use (biases, q/k norms) are NULL. */
+enum spiral_layer_slot {
+    SPIRAL_W_ATTN_NORM = 0, /* [d_model] fp32 */
+    SPIRAL_W_Q, SPIRAL_W_K, SPIRAL_W_V,      /* [Hq*hd, d], [Hkv*hd, d], [Hkv*hd, d] */
+    SPIRAL_W_BQ, SPIRAL_W_BK, SPIRAL_W_BV,   /* [Hq*hd], [Hkv*hd], [Hkv*hd] or NULL */
+    SPIRAL_W_Q_NORM, SPIRAL_W_K_NORM,        /* [hd] fp32 or NULL */
+    SPIRAL_W_O,                              /* [d, Hq*hd] */
+    SPIRAL_W_MLP_NORM,                       /* [d_model] fp32 */
+    SPIRAL_W_GATE, SPIRAL_W_UP,              /* [ffn, d] */
+    SPIRAL_W_DOWN,                           /* [d, ffn] */
+    SPIRAL_LAYER_SLOTS                       /* = 14 */
+};
+
+typedef struct spiral_model   spiral_model;
+typedef struct spiral_kv_pool spiral_kv_pool;
+typedef struct spiral_rae     spiral_rae;
+
+const char* spiral_last_error(void);
+const char* spiral_version(void);
+
+/* ---- model ------------------------------------------------------------------------------------
+ * Records the geometry and the caller's device weight pointers (no copy, no repack; the weights
+ * must stay valid and unchanged while the model is in use).  host_dev_weights: host array of
+ * n_weights = 3 + 14*n_layers device pointers in the order above, every matrix 16-byte aligned.
+ * Errors: INVALID_ARG (null / missing required pointer / misaligned / wrong n_weights),
+ * SHAPE (head_dim not in {32,64,128}; Hq not a multiple of Hkv or Hq/Hkv > 16; kv_block_tokens != 16;
+ * for bf16 weights: d_model, Hq*hd, ffn_dim not multiples of 32, or any projection width not a
+ * multiple of 16). */
+int  spiral_model_load(const spiral_model_config* cfg, const void* const* host_dev_weights,
+                       int n_weights, spiral_model** out);
+void spiral_model_free(spiral_model* m);
+
+/* Bytes of device workspace a prefill over at most max_rows packed prompt tokens, or a decode step
+ * over at most max_rows sequences whose context is at most max_context tokens, needs.
+ * Returns 0 on bad arguments. */
+size_t spiral_workspace_bytes(const spiral_model* m, int max_rows, int max_context);
+
+/* ---- paged KV cache ---------------------------------------------------------------------------
+ * One pool holds the K and V of every layer for up to max_seqs sequences in n_pages pages of 16
+ * tokens; a sequence owns at most max_blocks_per_seq pages.  Layout inside dev_mem (all managed by
+ * the library): block table int32 [max_seqs, max_blocks_per_seq], lengths int32 [max_seqs], then the
+ * pages, bf16: [layer][page][kv_head]{ K [16 tokens][head_dim] , V [head_dim][16 tokens] }.
+ * spiral_kv_pool_bytes gives the size dev_mem must have (0 on bad arguments); dev_mem must be
+ * 256-byte aligned.  host_page_order (n_pages distinct ids in [0,n_pages), or NULL for ascending)
+ * is the order in which free pages are handed out.  Creation enqueues a zero fill of the pool on
+ * `stream`.  Sequence ids are the integers [0, max_seqs); all start empty. */
+size_t spiral_kv_pool_bytes(const spiral_model* m, int n_pages, int max_seqs, int max_blocks_per_seq);
+int    spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_t bytes, int n_pages,
+                             int max_seqs, int max_blocks_per_seq, const int32_t* host_page_order,
+                             void* stream, spiral_kv_pool** out);
+void   spiral_kv_pool_free(spiral_kv_pool* p);
+/* Empties the listed sequences and returns their pages to the free list (in reverse order of use). */
+int    spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, int n, void* stream);
+/* Host-side view: tokens cached for a sequence (negative error code on a bad id); free pages. */
+int    spiral_seq_len(const spiral_kv_pool* p, int seq_id);
+int    spiral_kv_free_pages(const spiral_kv_pool* p);
+
+/* ---- prefill ----------------------------------------------------------------------------------
+ * Appends host_lens[i] >= 1 tokens to sequence host_seq_ids[i] (i < B; ids distinct) and returns the
+ * next-token logits after each sequence's last appended token.  A sequence may already hold a
+ * history (a new game turn appended to earlier turns): positions continue from its current length.
+ * dev_tokens_packed: int32 [sum(host_lens)], the sequences' tokens back to back, ids in [0, vocab).
+ * dev_logits: fp32 [B, vocab].  dev_ws/ws_bytes: workspace of at least
+ * spiral_workspace_bytes(m, sum(host_lens), longest resulting context), 256-byte aligned.
+ * Errors: INVALID_ARG, OOM_KV (pages, block-table slots or workspace too small), HIP. */
+int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids,
+                   const int32_t* host_lens, int B, const int32_t* dev_tokens_packed,
+                   void* dev_ws, size_t ws_bytes, float* dev_logits, void* stream);
+
+/* ---- decode step ------------------------------------------------------------------------------
+ * One autoregressive step for B distinct, non-empty sequences: sequence host_seq_ids[i] consumes
+ * token dev_in_tokens[i] at position = its current length, its K/V are appended to its pages, and
+ * dev_logits[i, :] (fp32 [B, vocab]) receives the logits of the token after it.  Input tokens are
+ * explicit so that a caller can feed back its own samples or force given tokens.
+ * Workspace as for prefill with rows = B.  Errors as for prefill. */
+int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                       const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes,
+                       float* dev_logits, void* stream);
+
+/* ---- sampling ---------------------------------------------------------------------------------
+ * dev_out_tokens[i] = argmax_v( dev_logits[i,v] / temperature + g[i,v] ), lowest index on ties, in
+ * fp32: an exact draw from softmax(logits / temperature) (Gumbel-max), the actor's untruncated
+ * categorical (hyper-parameter table, App. D).  temperature == 0 selects greedy decoding (g = 0).
+ * g is standard Gumbel noise -ln(-ln u): either read from dev_noise (fp32 [B, V], test mode) or,
+ * when dev_noise is NULL, generated from the stateless counter generator
+ *     mix(z): z^=z>>30; z*=0xBF58476D1CE4E5B9; z^=z>>27; z*=0x94D049BB133111EB; z^=z>>31   (mod 2^64)
+ *     key = mix(mix(seed ^ 0x9E3779B97F4A7C15) + ((uint64)seq_id << 32 | step))
+ *     r   = mix(key + v * 0x9E3779B97F4A7C15) >> 32 ;  u = ((r >> 9) + 0.5) * 2^-23
+ * with seq_id = host_seq_ids[i] and step = host_steps[i] (both >= 0).  B <= SPIRAL_MAX_BATCH.
+ * Errors: INVALID_ARG (null pointers, B or V < 1, temperature < 0 or not finite), HIP. */
+int spiral_sample(const float* dev_logits, int B, int V, float temperature, uint64_t seed,
+                  const int32_t* host_seq_ids, const int32_t* host_steps, const float* dev_noise,
+                  int32_t* dev_out_tokens, void* stream);
+
+/* ---- role-conditioned advantage estimation (host only, float64) -------------------------------
+ * Baselines b[game][role], role in {0,1}, start at 0 (Alg. 1, initialisation).  spiral_rae_update
+ * processes n finished trajectories in array order; for trajectory i with game host_game_id[i] and
+ * player-0 terminal reward host_r0[i] (player 1 receives -host_r0[i]: zero-sum), for role 0 then 1:
+ *     b <- alpha * b + (1 - alpha) * R_role ;   adv[i][role] = R_role - b     (the updated b)
+ * (Alg. 1, policy-optimisation loop; RAE equation, Sec. 3).  alpha in [0,1]; the paper uses 0.95.
+ * host_adv: [n][2].  get/set copy the whole table [n_games][2].
+ * Errors: INVALID_ARG (null, n < 0, game id out of range, alpha outside [0,1], non-finite reward);
+ * on error nothing is modified. */
+int  spiral_rae_create(int n_games, double alpha, spiral_rae** out);
+int  spiral_rae_update(spiral_rae* r, const int32_t* host_game_id, const double* host_r0, int n,
+                       double* host_adv);
+int  spiral_rae_get(const spiral_rae* r, double* host_b);
+int  spiral_rae_set(spiral_rae* r, const double* host_b);
+void spiral_rae_free(spiral_rae* r);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPIRAL_H */

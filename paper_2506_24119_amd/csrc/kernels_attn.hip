@@ -1,0 +1,253 @@
+// GQA attention over the paged KV cache on the gfx950 matrix cores.
+//
+// Page layout (per layer, page, kv head): K [16 tokens][hd] followed by V [hd][16 tokens], bf16.
+// Both are the layouts the MFMA operands want with plain 16-byte / 8-byte loads from HBM:
+//   S^T[token][row] = sum_d K[token][d] * Q[row][d]     v_mfma_f32_16x16x32_bf16, A = K page (a lane
+//                     reads 8 consecutive d of one token), B = the 16 query rows held in registers;
+//   O^T[d][row]    += sum_token V^T[d][token] * P^T[token][row]   v_mfma_f32_16x16x16_bf16, A = V page
+//                     (a lane reads 4 consecutive tokens of one d), B = P^T, which is exactly the
+//                     register layout S^T came out in, so probabilities never leave the lane.
+// A tile has 16 query rows.  Decode: the rows are the G = Hq/Hkv query heads that share one kv
+// head (padded to 16), so K and V are read once per group.  Prefill: the rows are 16 consecutive
+// positions of one query head, each with its own causal limit.
+//
+// One workgroup = one tile x a range of pages; its four waves take pages round-robin, each with a
+// private online softmax (running max m, sum l, unnormalised O), merged through LDS at the end.
+// Decode splits the context into chunks of `chunk_pages` pages (one workgroup each, so that ragged
+// lengths spread over all CUs) and a second small kernel merges the chunks' (m, l, O).
+// Softmax is evaluated in base 2: scores are scaled by log2(e)/sqrt(hd) and v_exp_f32 is 2^x.
+#include "spiral_internal.h"
+
+namespace spiral {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr float kNegBig = -1.0e30f;
+
+template <int HD>
+struct PageFrag {
+    u32x4 k[HD / 32];     // K: token = lane%16, d = ks*32 + (lane/16)*8 .. +8
+    u32x2 v[HD / 16];     // V^T: d = mt*16 + lane%16, tokens (lane/16)*4 .. +4
+};
+
+template <int HD>
+__device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, int li, int lg) {
+    const uint16_t* vp = kp + kPageTokens * HD;
+#pragma unroll
+    for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = *(const u32x4*)(kp + li * HD + ks * 32 + lg * 8);
+#pragma unroll
+    for (int mt = 0; mt < HD / 16; ++mt) f.v[mt] = *(const u32x2*)(vp + (mt * 16 + li) * kPageTokens + lg * 4);
+}
+
+template <int HD, bool PREFILL, bool ACT32>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
+    constexpr int KS = HD / 32, MT = HD / 16, OSTRIDE = HD + 4;
+    __shared__ float s_o[4][16 * OSTRIDE];
+    __shared__ float s_m[4][16];
+    __shared__ float s_l[4][16];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & 15, lg = lane >> 4;
+    const int G = a.n_q_heads / a.n_kv_heads;
+
+    int seq, kvh, p_begin, p_end, limit, n_valid_rows;
+    const uint16_t* qptr = nullptr;       // this lane's query row (row li of the tile) or null
+    int row0 = 0, head0 = 0;
+    if (PREFILL) {
+        const int b = blockIdx.z, h = blockIdx.y, qb = blockIdx.x;
+        const int r_first = a.cu_rows[b];
+        const int n_in_seq = a.cu_rows[b + 1] - r_first;
+        if (qb * 16 >= n_in_seq) return;
+        n_valid_rows = min(16, n_in_seq - qb * 16);
+        row0 = r_first + qb * 16;
+        head0 = h;
+        kvh = h / G;
+        seq = a.row_seq[row0];
+        const int pos0 = a.row_pos[row0];
+        limit = li < n_valid_rows ? pos0 + li : -1;
+        if (li < n_valid_rows) qptr = a.q + ((size_t)(row0 + li) * a.n_q_heads + h) * HD;
+        p_begin = 0;
+        p_end = (pos0 + n_valid_rows - 1) / kPageTokens + 1;
+    } else {
+        const int r = blockIdx.z, c = blockIdx.x;
+        kvh = blockIdx.y;
+        seq = a.row_seq[r];
+        const int pos = a.row_pos[r];
+        const int n_pages = pos / kPageTokens + 1;
+        p_begin = c * a.chunk_pages;
+        if (p_begin >= n_pages) return;
+        p_end = min(p_begin + a.chunk_pages, n_pages);
+        n_valid_rows = G;
+        row0 = r;
+        head0 = kvh * G;
+        limit = pos;
+        if (li < G) qptr = a.q + ((size_t)r * a.n_q_heads + kvh * G + li) * HD;
+    }
+
+    // query rows as the B operand: row = li, d = ks*32 + lg*8 .. +8
+    u32x4 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+        qf[ks] = qptr ? *(const u32x4*)(qptr + ks * 32 + lg * 8) : u32x4{0u, 0u, 0u, 0u};
+
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.f;
+
+    const int32_t* bt = a.block_table + (size_t)seq * a.max_blocks;
+    const size_t page_elems = (size_t)a.n_kv_heads * (2 * kPageTokens * HD);
+    const size_t head_off = (size_t)kvh * (2 * kPageTokens * HD);
+
+    auto step = [&](const PageFrag<HD>& f, int pi) {
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[ks]),
+                                                        __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
+        const int t0 = pi * kPageTokens + lg * 4;
+        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
+        bool ok[4];
+        float mx = kNegBig;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            ok[r] = (t0 + r) <= limit;
+            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        float p[4];
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
+            ps += p[r];
+        }
+        l_run = l_run * alpha + ps;
+        m_run = m_new;
+        s16x4 pb;
+        pb.x = (short)f32_to_bf16_bits(p[0]);
+        pb.y = (short)f32_to_bf16_bits(p[1]);
+        pb.z = (short)f32_to_bf16_bits(p[2]);
+        pb.w = (short)f32_to_bf16_bits(p[3]);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            f32x4 o = acc[mt];
+            o.x *= alpha; o.y *= alpha; o.z *= alpha; o.w *= alpha;
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, f.v[mt]), pb, o, 0, 0, 0);
+        }
+    };
+
+    // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed
+    int pi = p_begin + wave;
+    if (pi < p_end) {
+        PageFrag<HD> cur, nxt;
+        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, li, lg);
+        while (true) {
+            const int pn = pi + 4;
+            const bool more = pn < p_end;
+            if (more) load_page<HD>(nxt, a.pages + (size_t)bt[pn] * page_elems + head_off, li, lg);
+            step(cur, pi);
+            if (!more) break;
+            cur = nxt;
+            pi = pn;
+        }
+    }
+
+    // ---- merge the four waves
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (lg == 0) { s_m[wave][li] = m_run; s_l[wave][li] = l_run; }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const f32x4 o = acc[mt];
+        *(float4*)&s_o[wave][li * OSTRIDE + mt * 16 + lg * 4] = make_float4(o.x, o.y, o.z, o.w);
+    }
+    __syncthreads();
+
+    for (int e = threadIdx.x; e < 16 * HD; e += 256) {
+        const int j = e / HD, i = e % HD;
+        if (j >= n_valid_rows) continue;
+        const float M = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
+        float L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float sc = __builtin_amdgcn_exp2f(s_m[w][j] - M);
+            L += s_l[w][j] * sc;
+            O += s_o[w][j * OSTRIDE + i] * sc;
+        }
+        if (PREFILL) {
+            const size_t o_idx = ((size_t)(row0 + j) * a.n_q_heads + head0) * HD + i;
+            ActStore<ACT32>::put(a.out, o_idx, O / L);
+        } else {
+            float* dst = a.part + ((((size_t)row0 * a.n_kv_heads + kvh) * a.n_chunks + blockIdx.x) * G + j) * (HD + 2);
+            dst[i] = O;
+            if (i == 0) { dst[HD] = M; dst[HD + 1] = L; }
+        }
+    }
+}
+
+// merge the per-chunk partial results of one (row, query head)
+template <int HD, bool ACT32>
+__global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
+    const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int kvh = h / G, j = h % G;
+    const int n_pages = a.row_pos[r] / kPageTokens + 1;
+    const int n_chunks = (n_pages + a.chunk_pages - 1) / a.chunk_pages;
+    const float* base = a.part + (((size_t)r * a.n_kv_heads + kvh) * a.n_chunks * G + j) * (HD + 2);
+    const size_t cstride = (size_t)G * (HD + 2);
+    float M = kNegBig;
+    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, base[c * cstride + HD]);
+    float L = 0.f, O = 0.f;
+    for (int c = 0; c < n_chunks; ++c) {
+        const float sc = __builtin_amdgcn_exp2f(base[c * cstride + HD] - M);
+        L += base[c * cstride + HD + 1] * sc;
+        O += base[c * cstride + i] * sc;
+    }
+    ActStore<ACT32>::put(a.out, ((size_t)r * a.n_q_heads + h) * HD + i, O / L);
+}
+
+template <int HD, bool ACT32>
+static hipError_t decode_impl(const AttnArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((attn_kernel<HD, false, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((attn_combine_kernel<HD, ACT32>), dim3(a.n_rows, a.n_q_heads), dim3(HD), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
+    if (a.n_rows <= 0 || a.n_chunks <= 0 || a.n_q_heads / a.n_kv_heads > kMaxGroup) return hipErrorInvalidValue;
+    switch (hd) {
+        case 32:  return act32 ? decode_impl<32, true>(a, s) : decode_impl<32, false>(a, s);
+        case 64:  return act32 ? decode_impl<64, true>(a, s) : decode_impl<64, false>(a, s);
+        case 128: return act32 ? decode_impl<128, true>(a, s) : decode_impl<128, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+template <int HD, bool ACT32>
+static hipError_t prefill_impl(const AttnArgs& a, int B, int max_new, hipStream_t s) {
+    const int qblocks = (max_new + 15) / 16;
+    hipLaunchKernelGGL((attn_kernel<HD, true, ACT32>), dim3(qblocks, a.n_q_heads, B), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s) {
+    if (B <= 0 || max_new <= 0) return hipErrorInvalidValue;
+    switch (hd) {
+        case 32:  return act32 ? prefill_impl<32, true>(a, B, max_new, s) : prefill_impl<32, false>(a, B, max_new, s);
+        case 64:  return act32 ? prefill_impl<64, true>(a, B, max_new, s) : prefill_impl<64, false>(a, B, max_new, s);
+        case 128: return act32 ? prefill_impl<128, true>(a, B, max_new, s) : prefill_impl<128, false>(a, B, max_new, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace spiral

@@ -1,0 +1,336 @@
+// Small memory-bound kernels of the decode path: embedding + RMSNorm, residual-add + RMSNorm,
+// the fused q/k/v post-processing (bias | per-head RMSNorm, RoPE, KV append), the Gumbel-max
+// sampler, and the by-value uploads that keep the library free of device allocations.
+#include "spiral_internal.h"
+
+namespace spiral {
+
+// ---------------------------------------------------------------------------------------------
+// plumbing
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_zero_kernel(uint4* p, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const uint4 z = make_uint4(0, 0, 0, 0);
+    for (; i < n16; i += stride) p[i] = z;
+}
+
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+    if (bytes == 0) return hipSuccess;
+    size_t n16 = bytes / 16;          // callers pass multiples of 16
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)p, n16);
+    return hipGetLastError();
+}
+
+__global__ void upload_kernel(int32_t* dst, IntChunk c, int n) {
+    int i = threadIdx.x;
+    if (i < n) dst[i] = c.v[i];
+}
+
+hipError_t launch_upload(int32_t* dev_dst, const int32_t* host_src, int n, hipStream_t s) {
+    for (int off = 0; off < n; off += kUploadInts) {
+        IntChunk c;
+        int m = n - off < kUploadInts ? n - off : kUploadInts;
+        for (int i = 0; i < m; ++i) c.v[i] = host_src[off + i];
+        hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(kUploadInts), 0, s, dev_dst + off, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+__global__ void scatter_kernel(int32_t* base, PairChunk c, int n) {
+    int i = threadIdx.x;
+    if (i < n) base[c.idx[i]] = c.val[i];
+}
+
+hipError_t launch_scatter(int32_t* dev_base, const int32_t* host_idx, const int32_t* host_val, int n, hipStream_t s) {
+    const int per = kUploadInts / 2;
+    for (int off = 0; off < n; off += per) {
+        PairChunk c;
+        int m = n - off < per ? n - off : per;
+        for (int i = 0; i < m; ++i) { c.idx[i] = host_idx[off + i]; c.val[i] = host_val[off + i]; }
+        hipLaunchKernelGGL(scatter_kernel, dim3(1), dim3(per), 0, s, dev_base, c, m);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// row -> (sequence, position) for a packed prefill batch
+__global__ void prefill_meta_kernel(const int32_t* cu_rows, const int32_t* base_pos, const int32_t* seq_ids,
+                                    int B, int n_rows, int32_t* row_seq, int32_t* row_pos) {
+    int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    int lo = 0, hi = B - 1;              // largest b with cu_rows[b] <= r
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (cu_rows[mid] <= r) lo = mid; else hi = mid - 1;
+    }
+    row_seq[r] = seq_ids[lo];
+    row_pos[r] = base_pos[lo] + (r - cu_rows[lo]);
+}
+
+hipError_t launch_prefill_meta(const int32_t* cu_rows, const int32_t* base_pos, const int32_t* seq_ids, int B,
+                               int n_rows, int32_t* row_seq, int32_t* row_pos, hipStream_t s) {
+    hipLaunchKernelGGL(prefill_meta_kernel, dim3((n_rows + 255) / 256), dim3(256), 0, s,
+                       cu_rows, base_pos, seq_ids, B, n_rows, row_seq, row_pos);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// block reduction (256 threads)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    v = wave_sum(v);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float t = red[0] + red[1] + red[2] + red[3];
+    __syncthreads();
+    return t;
+}
+
+// ---------------------------------------------------------------------------------------------
+// embedding gather + first RMSNorm (+ positions and the RoPE table of this step)
+// One block per row.  h = x * rsqrt(mean(x^2) + eps) * gain.
+// ---------------------------------------------------------------------------------------------
+template <bool WBF16, bool ACT32>
+__global__ __launch_bounds__(256) void embed_norm_kernel(EmbedArgs a, RopeFreq f) {
+    __shared__ float red[4];
+    __shared__ int s_pos;
+    const int r = blockIdx.x;
+    if (a.decode) {
+        if (threadIdx.x == 0) {
+            const int seq = a.seq_ids[r];
+            const int pos = a.lens[seq];
+            a.lens[seq] = pos + 1;
+            a.row_seq[r] = seq;
+            a.row_pos[r] = pos;
+            s_pos = pos;
+        }
+    } else if (threadIdx.x == 0) {
+        s_pos = a.row_pos[r];
+    }
+    __syncthreads();
+    const int pos = s_pos;
+    if ((int)threadIdx.x < a.half_hd) {
+        double ang = (double)pos * f.inv_freq[threadIdx.x];
+        a.rope[(size_t)r * a.half_hd + threadIdx.x] = make_float2((float)cos(ang), (float)sin(ang));
+    }
+    int tok = a.tokens[r];
+    tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);   // ids are validated by the caller; stay in bounds regardless
+    float* x = a.x + (size_t)r * a.d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < a.d; i += 256) {
+        float v;
+        if (WBF16) v = bf16_bits_to_f32(((const uint16_t*)a.embed)[(size_t)tok * a.d + i]);
+        else v = ((const float*)a.embed)[(size_t)tok * a.d + i];
+        x[i] = v;
+        ss += v * v;
+    }
+    ss = block_sum_256(ss, red);
+    const float rs = rsqrtf(ss / (float)a.d + a.eps);
+    for (int i = threadIdx.x; i < a.d; i += 256)
+        ActStore<ACT32>::put(a.h, (size_t)r * a.d + i, x[i] * rs * a.gain[i]);
+}
+
+hipError_t launch_embed_norm(const EmbedArgs& a, const RopeFreq& f, bool w_bf16, bool act32, hipStream_t s) {
+    dim3 g(a.n_rows), b(256);
+    if (w_bf16 && !act32) hipLaunchKernelGGL((embed_norm_kernel<true, false>), g, b, 0, s, a, f);
+    else if (!w_bf16 && act32) hipLaunchKernelGGL((embed_norm_kernel<false, true>), g, b, 0, s, a, f);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// residual add of the split-K projection partials + RMSNorm.  One block per output row.
+// ---------------------------------------------------------------------------------------------
+template <bool ACT32>
+__global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
+    __shared__ float red[4];
+    const int ro = blockIdx.x;
+    const int ri = a.row_map ? a.row_map[ro] : ro;
+    float* x = a.x + (size_t)ri * a.d;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < a.d; i += 256) {
+        float v = x[i];
+        for (int p = 0; p < a.n_part; ++p) v += a.part[((size_t)p * a.rows_in + ri) * a.d + i];
+        if (a.n_part > 0) x[i] = v;
+        ss += v * v;
+    }
+    ss = block_sum_256(ss, red);
+    const float rs = rsqrtf(ss / (float)a.d + a.eps);
+    for (int i = threadIdx.x; i < a.d; i += 256)
+        ActStore<ACT32>::put(a.h, (size_t)ro * a.d + i, x[i] * rs * a.gain[i]);
+}
+
+hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s) {
+    dim3 g(a.rows_out), b(256);
+    if (act32) hipLaunchKernelGGL((add_norm_kernel<true>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((add_norm_kernel<false>), g, b, 0, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// q/k/v post-processing: sum the projection partials, add the bias, RMSNorm each q/k head over
+// head_dim (before RoPE), rotate q/k (rotate-half pairing), store q as bf16 and append k, v to the
+// sequence's page: K row-major [slot][hd], V transposed [hd][slot].
+// One wave per (row, head); lane p handles the pair (p, p + hd/2).
+// ---------------------------------------------------------------------------------------------
+template <bool WBF16>
+__global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
+    const int r = blockIdx.x;
+    const int head = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int n_heads = a.n_q_heads + 2 * a.n_kv_heads;
+    if (head >= n_heads) return;
+    const int hd = a.hd, half = hd >> 1;
+    const int width = n_heads * hd;
+    const bool is_q = head < a.n_q_heads;
+    const bool is_k = !is_q && head < a.n_q_heads + a.n_kv_heads;
+    const int kvh = is_q ? 0 : (is_k ? head - a.n_q_heads : head - a.n_q_heads - a.n_kv_heads);
+
+    const void* bias = is_q ? a.bq : (is_k ? a.bk : a.bv);
+    const int bias_off = (is_q ? head : kvh) * hd;
+    const float* gain = is_q ? a.q_gain : (is_k ? a.k_gain : nullptr);
+
+    const int pos = a.row_pos[r];
+    const int seq = a.row_seq[r];
+    const int slot = pos & (kPageTokens - 1);
+    size_t page_base = 0;
+    if (!is_q) {
+        const int page = a.block_table[(size_t)seq * a.max_blocks + (pos >> 4)];
+        page_base = ((size_t)page * a.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * hd);
+    }
+
+    for (int p = lane; p < ((half + 63) & ~63); p += 64) {
+        const bool act = p < half;
+        float lo = 0.f, hi = 0.f;
+        if (act) {
+            for (int s = 0; s < a.n_part; ++s) {
+                const float* src = a.qkv + ((size_t)s * a.n_rows + r) * width + (size_t)head * hd;
+                lo += src[p];
+                hi += src[p + half];
+            }
+            if (bias) {
+                if (WBF16) {
+                    lo += bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + p]);
+                    hi += bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + p + half]);
+                } else {
+                    lo += ((const float*)bias)[bias_off + p];
+                    hi += ((const float*)bias)[bias_off + p + half];
+                }
+            }
+        }
+        if (gain) {       // hd <= 128: the whole head sits in one pass of the wave
+            const float ss = wave_sum(lo * lo + hi * hi);
+            const float rs = rsqrtf(ss / (float)hd + a.eps);
+            if (act) { lo = lo * rs * gain[p]; hi = hi * rs * gain[p + half]; }
+        }
+        if (!act) continue;
+        if (is_q || is_k) {
+            const float2 cs = a.rope[(size_t)r * half + p];
+            const float nlo = lo * cs.x - hi * cs.y;
+            const float nhi = hi * cs.x + lo * cs.y;
+            lo = nlo; hi = nhi;
+        }
+        if (is_q) {
+            uint16_t* q = a.q + ((size_t)r * a.n_q_heads + head) * hd;
+            q[p] = f32_to_bf16_bits(lo);
+            q[p + half] = f32_to_bf16_bits(hi);
+        } else if (is_k) {
+            uint16_t* K = a.pages + page_base + (size_t)slot * hd;
+            K[p] = f32_to_bf16_bits(lo);
+            K[p + half] = f32_to_bf16_bits(hi);
+        } else {
+            uint16_t* V = a.pages + page_base + (size_t)kPageTokens * hd;
+            V[(size_t)p * kPageTokens + slot] = f32_to_bf16_bits(lo);
+            V[(size_t)(p + half) * kPageTokens + slot] = f32_to_bf16_bits(hi);
+        }
+    }
+}
+
+hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s) {
+    const int n_heads = a.n_q_heads + 2 * a.n_kv_heads;
+    dim3 g(a.n_rows, (n_heads + 3) / 4), b(256);
+    if (w_bf16) hipLaunchKernelGGL((qkv_post_kernel<true>), g, b, 0, s, a);
+    else hipLaunchKernelGGL((qkv_post_kernel<false>), g, b, 0, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gumbel-max sampler: token = argmax_v(logit_v / T + g_v), lowest index on ties; T == 0 => greedy.
+// One block of 1024 threads per row; every thread scans a strided slice, then a wave shuffle
+// reduction and a 16-entry LDS reduction pick the winner.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+    return v > bv || (v == bv && i < bi);
+}
+
+__global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int V, float temperature, int mode,
+                                                      KeyChunk keys, const float* noise, int32_t* out) {
+    // mode 0: greedy; 1: generated noise; 2: noise buffer
+    __shared__ float s_v[16];
+    __shared__ int s_i[16];
+    const int row = blockIdx.x;
+    const float* lr = logits + (size_t)row * V;
+    const float* nr = noise ? noise + (size_t)row * V : nullptr;
+    const uint64_t key = keys.key[row];
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int v = threadIdx.x; v < V; v += 1024) {
+        float sc = lr[v];
+        if (mode != 0) {
+            float g;
+            if (mode == 2) {
+                g = nr[v];
+            } else {
+                const uint32_t r = (uint32_t)(mix64(key + (uint64_t)v * 0x9E3779B97F4A7C15ull) >> 32);
+                const float u = ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;   // 2^-23
+                g = -logf(-logf(u));
+            }
+            sc = sc / temperature + g;      // IEEE division, as the definition states it
+        }
+        if (better(sc, v, bv, bi)) { bv = sc; bi = v; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+        out[row] = bi == 0x7FFFFFFF ? 0 : bi;
+    }
+}
+
+hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
+                         const float* noise, int32_t* out, hipStream_t s) {
+    const int mode = temperature == 0.0f ? 0 : (noise ? 2 : 1);
+    for (int off = 0; off < B; off += 128) {
+        KeyChunk k;
+        const int m = B - off < 128 ? B - off : 128;
+        for (int i = 0; i < m; ++i) k.key[i] = host_keys ? host_keys[off + i] : 0;
+        hipLaunchKernelGGL(sample_kernel, dim3(m), dim3(1024), 0, s, logits + (size_t)off * V, V, temperature, mode,
+                           k, noise ? noise + (size_t)off * V : nullptr, out + off);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace spiral

@@ -1,0 +1,556 @@
+// Host side of the C ABI: argument checking, the paged-KV bookkeeping, workspace carving and the
+// fixed kernel sequence of a prefill / decode step.  No device memory is allocated here.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "spiral_internal.h"
+
+using namespace spiral;
+
+// ---------------------------------------------------------------------------------------------
+// errors
+// ---------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) return fail(SPIRAL_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+extern "C" const char* spiral_last_error(void) { return g_err; }
+int spiral_set_error(int code, const char* text) { return fail(code, "%s", text); }
+extern "C" const char* spiral_version(void) {
+#if SPIRAL_ACT_F16
+    return "spiral-mi355x 0.1 (gfx950; f16 MFMA activations, bf16 weights/KV)";
+#else
+    return "spiral-mi355x 0.1 (gfx950; bf16 MFMA activations, bf16 weights/KV)";
+#endif
+}
+
+// ---------------------------------------------------------------------------------------------
+// objects
+// ---------------------------------------------------------------------------------------------
+struct Tune {
+    int bn_qkv = 32, s_qkv = 2;
+    int bn_o = 32, s_o = 4;
+    int bn_gu = 64;
+    int bn_down = 32, s_down = 4;
+    int bn_lm = 64;
+    int chunk_pages = 16;
+};
+constexpr int kMaxSplit = 8;
+
+struct spiral_model {
+    spiral_model_config cfg;
+    std::vector<const void*> w;
+    bool w_bf16;
+    RopeFreq freq;
+    Tune tune;
+    const void* lw(int layer, int slot) const { return w[3 + layer * SPIRAL_LAYER_SLOTS + slot]; }
+};
+
+struct spiral_kv_pool {
+    const spiral_model* m;
+    int32_t* d_block_table;
+    int32_t* d_lens;
+    uint16_t* d_pages;
+    int n_pages, max_seqs, max_blocks;
+    size_t layer_elems;                       // elements between consecutive layers' page arrays
+    std::vector<int32_t> free_list;           // back = next page handed out
+    std::vector<int32_t> h_lens;
+    std::vector<std::vector<int32_t>> h_pages;
+    std::vector<int32_t> uploaded_ids;        // seq ids currently sitting in the workspace
+    const void* uploaded_ws = nullptr;
+};
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static void parse_tune(Tune& t) {
+    const char* e = getenv("SPIRAL_TUNE");
+    if (!e) return;
+    std::string s(e);
+    size_t i = 0;
+    while (i < s.size()) {
+        size_t j = s.find(',', i);
+        if (j == std::string::npos) j = s.size();
+        std::string kv = s.substr(i, j - i);
+        size_t eq = kv.find('=');
+        if (eq != std::string::npos) {
+            std::string k = kv.substr(0, eq);
+            int a = 0, b = 0;
+            int n = sscanf(kv.c_str() + eq + 1, "%d:%d", &a, &b);
+            if (n >= 1) {
+                if (k == "qkv") { t.bn_qkv = a; if (n == 2) t.s_qkv = b; }
+                else if (k == "o") { t.bn_o = a; if (n == 2) t.s_o = b; }
+                else if (k == "gu") { t.bn_gu = a; }
+                else if (k == "down") { t.bn_down = a; if (n == 2) t.s_down = b; }
+                else if (k == "lm") { t.bn_lm = a; }
+                else if (k == "chunk") { t.chunk_pages = a; }
+            }
+        }
+        i = j + 1;
+    }
+    auto clampi = [](int& v, int lo, int hi) { v = v < lo ? lo : (v > hi ? hi : v); };
+    clampi(t.s_qkv, 1, kMaxSplit); clampi(t.s_o, 1, kMaxSplit); clampi(t.s_down, 1, kMaxSplit);
+    clampi(t.chunk_pages, 1, 1 << 20);
+}
+
+extern "C" int spiral_model_load(const spiral_model_config* cfg, const void* const* host_dev_weights,
+                                 int n_weights, spiral_model** out) {
+    if (!cfg || !host_dev_weights || !out) return fail(SPIRAL_ERR_INVALID_ARG, "model_load: null argument");
+    *out = nullptr;
+    const spiral_model_config& c = *cfg;
+    if (c.n_layers < 1 || c.d_model < 1 || c.n_q_heads < 1 || c.n_kv_heads < 1 || c.ffn_dim < 1 || c.vocab < 1)
+        return fail(SPIRAL_ERR_SHAPE, "model_load: non-positive dimension");
+    if (c.head_dim != 32 && c.head_dim != 64 && c.head_dim != 128)
+        return fail(SPIRAL_ERR_SHAPE, "model_load: head_dim %d not in {32,64,128}", c.head_dim);
+    if (c.n_q_heads % c.n_kv_heads != 0 || c.n_q_heads / c.n_kv_heads > kMaxGroup)
+        return fail(SPIRAL_ERR_SHAPE, "model_load: %d query heads per kv head unsupported", c.n_q_heads / std::max(1, c.n_kv_heads));
+    if (c.kv_block_tokens != kPageTokens) return fail(SPIRAL_ERR_SHAPE, "model_load: kv_block_tokens must be 16");
+    if (c.weight_dtype != SPIRAL_WEIGHT_FP32 && c.weight_dtype != SPIRAL_WEIGHT_BF16)
+        return fail(SPIRAL_ERR_SHAPE, "model_load: unknown weight_dtype %d", c.weight_dtype);
+    if (!(c.rope_theta > 0.f) || !(c.rms_eps >= 0.f)) return fail(SPIRAL_ERR_INVALID_ARG, "model_load: bad rope_theta / rms_eps");
+    if (c.weight_dtype == SPIRAL_WEIGHT_BF16) {
+        const int qw = c.n_q_heads * c.head_dim;
+        if (c.d_model % 32 || qw % 32 || c.ffn_dim % 32)
+            return fail(SPIRAL_ERR_SHAPE, "model_load: d_model, Hq*hd and ffn_dim must be multiples of 32 for bf16 weights");
+        if (c.vocab % 4) return fail(SPIRAL_ERR_SHAPE, "model_load: vocab must be a multiple of 4 for bf16 weights");
+    }
+    if (n_weights != 3 + SPIRAL_LAYER_SLOTS * c.n_layers)
+        return fail(SPIRAL_ERR_INVALID_ARG, "model_load: expected %d weight pointers, got %d", 3 + SPIRAL_LAYER_SLOTS * c.n_layers, n_weights);
+    auto need = [&](int idx, bool required) -> bool {
+        const void* p = host_dev_weights[idx];
+        if (!p) return !required;
+        return ((uintptr_t)p & 15) == 0;
+    };
+    for (int i = 0; i < 3; ++i)
+        if (!need(i, true)) return fail(SPIRAL_ERR_INVALID_ARG, "model_load: weight %d null or not 16-byte aligned", i);
+    for (int l = 0; l < c.n_layers; ++l)
+        for (int s = 0; s < SPIRAL_LAYER_SLOTS; ++s) {
+            bool req = true;
+            if (s == SPIRAL_W_BQ || s == SPIRAL_W_BK || s == SPIRAL_W_BV) req = c.qkv_bias != 0;
+            if (s == SPIRAL_W_Q_NORM || s == SPIRAL_W_K_NORM) req = c.qk_norm != 0;
+            if (!need(3 + l * SPIRAL_LAYER_SLOTS + s, req))
+                return fail(SPIRAL_ERR_INVALID_ARG, "model_load: layer %d slot %d null or not 16-byte aligned", l, s);
+        }
+    spiral_model* m = new (std::nothrow) spiral_model();
+    if (!m) return fail(SPIRAL_ERR_INVALID_ARG, "model_load: out of host memory");
+    m->cfg = c;
+    m->w.assign(host_dev_weights, host_dev_weights + n_weights);
+    m->w_bf16 = c.weight_dtype == SPIRAL_WEIGHT_BF16;
+    for (int j = 0; j < 64; ++j)
+        m->freq.inv_freq[j] = j < c.head_dim / 2 ? std::pow((double)c.rope_theta, -2.0 * j / c.head_dim) : 0.0;
+    parse_tune(m->tune);
+    *out = m;
+    return SPIRAL_OK;
+}
+
+extern "C" void spiral_model_free(spiral_model* m) { delete m; }
+
+// ---------------------------------------------------------------------------------------------
+// workspace
+// ---------------------------------------------------------------------------------------------
+struct Workspace {
+    float* x; void* h; float* qkv; uint16_t* q; void* o; float* proj; void* mlp; void* hf;
+    float* attn_part; float2* rope;
+    int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows;
+    size_t bytes;
+};
+
+static int decode_chunks(const spiral_model* m, int max_context) {
+    const int pages = (max_context + kPageTokens - 1) / kPageTokens;
+    return std::max(1, (pages + m->tune.chunk_pages - 1) / m->tune.chunk_pages);
+}
+
+static Workspace carve(const spiral_model* m, char* base, int rows, int max_context) {
+    const spiral_model_config& c = m->cfg;
+    const size_t act = m->w_bf16 ? 2 : 4;
+    const size_t R = (size_t)rows;
+    const size_t brows = (size_t)std::min(rows, SPIRAL_MAX_BATCH);
+    const size_t nqkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    const size_t qw = (size_t)c.n_q_heads * c.head_dim;
+    const int G = c.n_q_heads / c.n_kv_heads;
+    // projection outputs: up to kMaxSplit K-split partials while rows <= 128, one copy beyond that;
+    // sized so that a workspace for R rows also serves any smaller row count
+    const size_t split_rows = std::max(R, std::min<size_t>(R, 128) * kMaxSplit);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { char* p = base ? base + off : nullptr; off += align256(bytes); return p; };
+    Workspace w;
+    // the per-call id arrays come first so that their addresses do not depend on rows / context
+    w.seq_ids = (int32_t*)take(SPIRAL_MAX_BATCH * 4);
+    w.cu_rows = (int32_t*)take((SPIRAL_MAX_BATCH + 1) * 4);
+    w.base_pos = (int32_t*)take(SPIRAL_MAX_BATCH * 4);
+    w.last_rows = (int32_t*)take(SPIRAL_MAX_BATCH * 4);
+    w.x = (float*)take(R * c.d_model * 4);
+    w.h = take(R * c.d_model * act);
+    w.qkv = (float*)take(split_rows * nqkv * 4);
+    w.q = (uint16_t*)take(R * qw * 2);
+    w.o = take(R * qw * act);
+    w.proj = (float*)take(split_rows * c.d_model * 4);
+    w.mlp = take(R * c.ffn_dim * act);
+    w.hf = take(brows * c.d_model * act);
+    w.rope = (float2*)take(R * (c.head_dim / 2) * 8);
+    w.row_seq = (int32_t*)take(R * 4);
+    w.row_pos = (int32_t*)take(R * 4);
+    w.attn_part = (float*)take(brows * c.n_kv_heads * decode_chunks(m, max_context) * G * (c.head_dim + 2) * 4);
+    w.bytes = off;
+    return w;
+}
+
+extern "C" size_t spiral_workspace_bytes(const spiral_model* m, int max_rows, int max_context) {
+    if (!m || max_rows < 1 || max_context < 1) return 0;
+    return carve(m, nullptr, max_rows, max_context).bytes;
+}
+
+// ---------------------------------------------------------------------------------------------
+// KV pool
+// ---------------------------------------------------------------------------------------------
+static size_t pool_header_bytes(int max_seqs, int max_blocks) {
+    return align256((size_t)max_seqs * max_blocks * 4) + align256((size_t)max_seqs * 4);
+}
+static size_t page_layer_elems(const spiral_model* m) {      // elements of one page in one layer
+    return (size_t)m->cfg.n_kv_heads * 2 * kPageTokens * m->cfg.head_dim;
+}
+
+extern "C" size_t spiral_kv_pool_bytes(const spiral_model* m, int n_pages, int max_seqs, int max_blocks_per_seq) {
+    if (!m || n_pages < 1 || max_seqs < 1 || max_blocks_per_seq < 1) return 0;
+    return pool_header_bytes(max_seqs, max_blocks_per_seq) +
+           (size_t)m->cfg.n_layers * n_pages * page_layer_elems(m) * 2;
+}
+
+extern "C" int spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_t bytes, int n_pages, int max_seqs,
+                                     int max_blocks_per_seq, const int32_t* host_page_order, void* stream,
+                                     spiral_kv_pool** out) {
+    if (!out) return fail(SPIRAL_ERR_INVALID_ARG, "kv_pool_create: null out");
+    *out = nullptr;
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "kv_pool_create: null model");
+    if (!dev_mem || ((uintptr_t)dev_mem & 255)) return fail(SPIRAL_ERR_INVALID_ARG, "kv_pool_create: dev_mem null or not 256-byte aligned");
+    const size_t need = spiral_kv_pool_bytes(m, n_pages, max_seqs, max_blocks_per_seq);
+    if (need == 0) return fail(SPIRAL_ERR_INVALID_ARG, "kv_pool_create: non-positive size argument");
+    if (bytes < need) return fail(SPIRAL_ERR_OOM_KV, "kv_pool_create: %zu bytes given, %zu needed", bytes, need);
+    std::vector<int32_t> order(n_pages);
+    if (host_page_order) {
+        std::vector<char> seen(n_pages, 0);
+        for (int i = 0; i < n_pages; ++i) {
+            const int p = host_page_order[i];
+            if (p < 0 || p >= n_pages || seen[p]) return fail(SPIRAL_ERR_INVALID_ARG, "kv_pool_create: page order is not a permutation");
+            seen[p] = 1;
+            order[i] = p;
+        }
+    } else {
+        for (int i = 0; i < n_pages; ++i) order[i] = i;
+    }
+    spiral_kv_pool* p = new (std::nothrow) spiral_kv_pool();
+    if (!p) return fail(SPIRAL_ERR_INVALID_ARG, "kv_pool_create: out of host memory");
+    p->m = m;
+    char* base = (char*)dev_mem;
+    p->d_block_table = (int32_t*)base;
+    p->d_lens = (int32_t*)(base + align256((size_t)max_seqs * max_blocks_per_seq * 4));
+    p->d_pages = (uint16_t*)(base + pool_header_bytes(max_seqs, max_blocks_per_seq));
+    p->n_pages = n_pages; p->max_seqs = max_seqs; p->max_blocks = max_blocks_per_seq;
+    p->layer_elems = (size_t)n_pages * page_layer_elems(m);
+    p->free_list.assign(order.rbegin(), order.rend());     // order[0] is handed out first
+    p->h_lens.assign(max_seqs, 0);
+    p->h_pages.assign(max_seqs, std::vector<int32_t>());
+    hipError_t e = launch_fill_zero(dev_mem, need, (hipStream_t)stream);
+    if (e != hipSuccess) { delete p; return fail(SPIRAL_ERR_HIP, "kv_pool_create: fill: %s", hipGetErrorString(e)); }
+    *out = p;
+    return SPIRAL_OK;
+}
+
+extern "C" void spiral_kv_pool_free(spiral_kv_pool* p) { delete p; }
+
+static int check_ids(const spiral_kv_pool* p, const int32_t* ids, int n, const char* who) {
+    if (!ids) return fail(SPIRAL_ERR_INVALID_ARG, "%s: null sequence ids", who);
+    if (n < 1 || n > SPIRAL_MAX_BATCH) return fail(SPIRAL_ERR_INVALID_ARG, "%s: batch %d outside [1, %d]", who, n, SPIRAL_MAX_BATCH);
+    std::vector<char> seen(p->max_seqs, 0);
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= p->max_seqs) return fail(SPIRAL_ERR_INVALID_ARG, "%s: sequence id %d out of range", who, ids[i]);
+        if (seen[ids[i]]) return fail(SPIRAL_ERR_INVALID_ARG, "%s: sequence id %d listed twice", who, ids[i]);
+        seen[ids[i]] = 1;
+    }
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, int n, void* stream) {
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "seq_reset: null pool");
+    if (n == 0) return SPIRAL_OK;
+    int rc = check_ids(p, host_seq_ids, n, "seq_reset");
+    if (rc) return rc;
+    std::vector<int32_t> idx(n), val(n, 0);
+    for (int i = 0; i < n; ++i) idx[i] = host_seq_ids[i];
+    HIP_TRY(launch_scatter(p->d_lens, idx.data(), val.data(), n, (hipStream_t)stream));
+    for (int i = 0; i < n; ++i) {
+        std::vector<int32_t>& pg = p->h_pages[host_seq_ids[i]];
+        for (size_t k = pg.size(); k-- > 0;) p->free_list.push_back(pg[k]);
+        pg.clear();
+        p->h_lens[host_seq_ids[i]] = 0;
+    }
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_seq_len(const spiral_kv_pool* p, int seq_id) {
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "seq_len: null pool");
+    if (seq_id < 0 || seq_id >= p->max_seqs) return fail(SPIRAL_ERR_INVALID_ARG, "seq_len: id %d out of range", seq_id);
+    return p->h_lens[seq_id];
+}
+
+extern "C" int spiral_kv_free_pages(const spiral_kv_pool* p) {
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "kv_free_pages: null pool");
+    return (int)p->free_list.size();
+}
+
+// Checks that every listed sequence can grow by add[i] tokens, then takes the pages and enqueues the
+// block-table updates.  Nothing is modified when the check fails.
+static int grow(spiral_kv_pool* p, const int32_t* ids, const int32_t* add, int n, hipStream_t s, const char* who) {
+    size_t need_pages = 0;
+    for (int i = 0; i < n; ++i) {
+        const long long new_len = (long long)p->h_lens[ids[i]] + add[i];
+        const long long blocks = (new_len + kPageTokens - 1) / kPageTokens;
+        if (blocks > p->max_blocks)
+            return fail(SPIRAL_ERR_OOM_KV, "%s: sequence %d would need %lld pages, block table holds %d", who, ids[i], blocks, p->max_blocks);
+        need_pages += (size_t)blocks - p->h_pages[ids[i]].size();
+    }
+    if (need_pages > p->free_list.size())
+        return fail(SPIRAL_ERR_OOM_KV, "%s: %zu pages needed, %zu free", who, need_pages, p->free_list.size());
+    std::vector<int32_t> idx, val;
+    for (int i = 0; i < n; ++i) {
+        const int new_len = p->h_lens[ids[i]] + add[i];
+        const size_t blocks = (size_t)(new_len + kPageTokens - 1) / kPageTokens;
+        std::vector<int32_t>& pg = p->h_pages[ids[i]];
+        while (pg.size() < blocks) {
+            const int32_t page = p->free_list.back();
+            p->free_list.pop_back();
+            idx.push_back(ids[i] * p->max_blocks + (int32_t)pg.size());
+            val.push_back(page);
+            pg.push_back(page);
+        }
+    }
+    if (!idx.empty()) HIP_TRY(launch_scatter(p->d_block_table, idx.data(), val.data(), (int)idx.size(), s));
+    return SPIRAL_OK;
+}
+
+static int upload_ids(spiral_kv_pool* p, const Workspace& w, const void* ws, const int32_t* ids, int n, hipStream_t s) {
+    if (p->uploaded_ws == ws && (int)p->uploaded_ids.size() == n && std::equal(ids, ids + n, p->uploaded_ids.begin()))
+        return SPIRAL_OK;
+    HIP_TRY(launch_upload(w.seq_ids, ids, n, s));
+    p->uploaded_ids.assign(ids, ids + n);
+    p->uploaded_ws = ws;
+    return SPIRAL_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// the layer stack (shared by prefill and decode)
+// ---------------------------------------------------------------------------------------------
+struct StepCtx {
+    spiral_model* m; spiral_kv_pool* p; Workspace w; hipStream_t s;
+    int rows;            // activation rows
+    int B;               // sequences
+    bool decode;
+    int max_new;         // prefill: longest appended run
+    int n_chunks;        // decode: context chunks
+    float* logits;
+};
+
+static int run_layers(StepCtx& c) {
+    spiral_model* m = c.m;
+    const spiral_model_config& cfg = m->cfg;
+    const bool act32 = !m->w_bf16;
+    const Tune& t = m->tune;
+    const int d = cfg.d_model, hd = cfg.head_dim;
+    const int qw = cfg.n_q_heads * hd, kw = cfg.n_kv_heads * hd, nqkv = qw + 2 * kw;
+    const bool wide = c.rows > 128 || act32;      // many row tiles already fill the GPU: no K split
+    const int s_qkv = wide ? 1 : t.s_qkv, s_o = wide ? 1 : t.s_o, s_down = wide ? 1 : t.s_down;
+    int pending = 0;            // projection partials waiting to be added to the residual
+
+    for (int l = 0; l < cfg.n_layers; ++l) {
+        if (l > 0) {
+            NormArgs n = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_ATTN_NORM), c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps};
+            HIP_TRY(launch_add_norm(n, act32, c.s));
+        }
+        GemmArgs g = {};
+        g.A = c.w.h; g.w[0] = m->lw(l, SPIRAL_W_Q); g.w[1] = m->lw(l, SPIRAL_W_K); g.w[2] = m->lw(l, SPIRAL_W_V);
+        g.rows[0] = qw; g.rows[1] = kw; g.rows[2] = kw;
+        g.M = c.rows; g.N = nqkv; g.K = d; g.out = c.w.qkv; g.splits = s_qkv;
+        HIP_TRY(launch_gemm(g, EPI_STORE_F32, m->w_bf16, t.bn_qkv, c.s));
+
+        uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
+        QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
+                          (const float*)m->lw(l, SPIRAL_W_Q_NORM), (const float*)m->lw(l, SPIRAL_W_K_NORM),
+                          c.w.rope, c.w.row_seq, c.w.row_pos, c.p->d_block_table, c.w.q, pages,
+                          c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps};
+        HIP_TRY(launch_qkv_post(qa, m->w_bf16, c.s));
+
+        AttnArgs aa = {};
+        aa.q = c.w.q; aa.pages = pages; aa.block_table = c.p->d_block_table; aa.row_seq = c.w.row_seq;
+        aa.row_pos = c.w.row_pos; aa.cu_rows = c.w.cu_rows; aa.part = c.w.attn_part; aa.out = c.w.o;
+        aa.n_rows = c.rows; aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
+        aa.max_blocks = c.p->max_blocks; aa.chunk_pages = t.chunk_pages; aa.n_chunks = c.n_chunks;
+        aa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
+        if (c.decode) HIP_TRY(launch_attn_decode(aa, hd, act32, c.s));
+        else HIP_TRY(launch_attn_prefill(aa, hd, c.B, c.max_new, act32, c.s));
+
+        GemmArgs go = {};
+        go.A = c.w.o; go.w[0] = m->lw(l, SPIRAL_W_O); go.rows[0] = d;
+        go.M = c.rows; go.N = d; go.K = qw; go.out = c.w.proj; go.splits = s_o;
+        HIP_TRY(launch_gemm(go, EPI_STORE_F32, m->w_bf16, t.bn_o, c.s));
+
+        NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps};
+        HIP_TRY(launch_add_norm(n2, act32, c.s));
+
+        GemmArgs gu = {};
+        gu.A = c.w.h; gu.w[0] = m->lw(l, SPIRAL_W_GATE); gu.w[1] = m->lw(l, SPIRAL_W_UP);
+        gu.rows[0] = cfg.ffn_dim; gu.rows[1] = cfg.ffn_dim;
+        gu.M = c.rows; gu.N = cfg.ffn_dim; gu.K = d; gu.out = c.w.mlp; gu.splits = 1;
+        HIP_TRY(launch_gemm(gu, EPI_SWIGLU, m->w_bf16, t.bn_gu, c.s));
+
+        GemmArgs gd = {};
+        gd.A = c.w.mlp; gd.w[0] = m->lw(l, SPIRAL_W_DOWN); gd.rows[0] = d;
+        gd.M = c.rows; gd.N = d; gd.K = cfg.ffn_dim; gd.out = c.w.proj; gd.splits = s_down;
+        HIP_TRY(launch_gemm(gd, EPI_STORE_F32, m->w_bf16, t.bn_down, c.s));
+        pending = s_down;
+    }
+    // final norm on one row per sequence, then the LM head
+    NormArgs nf = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.hf, c.decode ? nullptr : c.w.last_rows,
+                   c.rows, c.B, d, pending, cfg.rms_eps};
+    HIP_TRY(launch_add_norm(nf, act32, c.s));
+    GemmArgs gl = {};
+    gl.A = c.w.hf; gl.w[0] = m->w[2]; gl.rows[0] = cfg.vocab;
+    gl.M = c.B; gl.N = cfg.vocab; gl.K = d; gl.out = c.logits; gl.splits = 1;
+    HIP_TRY(launch_gemm(gl, EPI_STORE_F32, m->w_bf16, t.bn_lm, c.s));
+    return SPIRAL_OK;
+}
+
+static int check_common(spiral_model* m, spiral_kv_pool* p, const void* toks, void* ws, float* logits, const char* who) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null model", who);
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null pool", who);
+    if (p->m != m) return fail(SPIRAL_ERR_INVALID_ARG, "%s: pool belongs to another model", who);
+    if (!toks || !logits) return fail(SPIRAL_ERR_INVALID_ARG, "%s: null token or logits pointer", who);
+    if (!ws || ((uintptr_t)ws & 255)) return fail(SPIRAL_ERR_INVALID_ARG, "%s: workspace null or not 256-byte aligned", who);
+    if ((uintptr_t)logits & 15) return fail(SPIRAL_ERR_INVALID_ARG, "%s: logits not 16-byte aligned", who);
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
+                              int B, const int32_t* dev_tokens_packed, void* dev_ws, size_t ws_bytes, float* dev_logits,
+                              void* stream) {
+    int rc = check_common(m, p, dev_tokens_packed, dev_ws, dev_logits, "prefill");
+    if (rc) return rc;
+    rc = check_ids(p, host_seq_ids, B, "prefill");
+    if (rc) return rc;
+    if (!host_lens) return fail(SPIRAL_ERR_INVALID_ARG, "prefill: null lengths");
+    long long rows = 0;
+    int max_new = 0, max_ctx = 0;
+    for (int i = 0; i < B; ++i) {
+        if (host_lens[i] < 1) return fail(SPIRAL_ERR_INVALID_ARG, "prefill: length %d of sequence %d is not positive", host_lens[i], host_seq_ids[i]);
+        rows += host_lens[i];
+        max_new = std::max(max_new, host_lens[i]);
+        const long long ctx = (long long)p->h_lens[host_seq_ids[i]] + host_lens[i];
+        if (ctx > (long long)p->max_blocks * kPageTokens)
+            return fail(SPIRAL_ERR_OOM_KV, "prefill: sequence %d would exceed its block table", host_seq_ids[i]);
+        max_ctx = std::max(max_ctx, (int)ctx);
+    }
+    if (rows > (1ll << 30)) return fail(SPIRAL_ERR_SHAPE, "prefill: too many tokens");
+    const size_t need = carve(m, nullptr, (int)rows, max_ctx).bytes;
+    if (ws_bytes < need) return fail(SPIRAL_ERR_OOM_KV, "prefill: workspace of %zu bytes given, %zu needed", ws_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    rc = grow(p, host_seq_ids, host_lens, B, s, "prefill");
+    if (rc) return rc;
+
+    Workspace w = carve(m, (char*)dev_ws, (int)rows, max_ctx);
+    std::vector<int32_t> cu(B + 1), base(B), last(B), new_len(B), ids(host_seq_ids, host_seq_ids + B);
+    cu[0] = 0;
+    for (int i = 0; i < B; ++i) {
+        cu[i + 1] = cu[i] + host_lens[i];
+        base[i] = p->h_lens[ids[i]];
+        last[i] = cu[i + 1] - 1;
+        new_len[i] = base[i] + host_lens[i];
+    }
+    rc = upload_ids(p, w, dev_ws, ids.data(), B, s);
+    if (rc) return rc;
+    HIP_TRY(launch_upload(w.cu_rows, cu.data(), B + 1, s));
+    HIP_TRY(launch_upload(w.base_pos, base.data(), B, s));
+    HIP_TRY(launch_upload(w.last_rows, last.data(), B, s));
+    HIP_TRY(launch_scatter(p->d_lens, ids.data(), new_len.data(), B, s));
+    HIP_TRY(launch_prefill_meta(w.cu_rows, w.base_pos, w.seq_ids, B, (int)rows, w.row_seq, w.row_pos, s));
+    for (int i = 0; i < B; ++i) p->h_lens[ids[i]] = new_len[i];
+
+    EmbedArgs e = {dev_tokens_packed, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h, nullptr, nullptr,
+                   w.row_seq, w.row_pos, w.rope, (int)rows, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab,
+                   m->cfg.rms_eps, 0};
+    HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
+    StepCtx c = {m, p, w, s, (int)rows, B, false, max_new, 1, dev_logits};
+    return run_layers(c);
+}
+
+extern "C" int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                                  const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float* dev_logits,
+                                  void* stream) {
+    int rc = check_common(m, p, dev_in_tokens, dev_ws, dev_logits, "decode_step");
+    if (rc) return rc;
+    rc = check_ids(p, host_seq_ids, B, "decode_step");
+    if (rc) return rc;
+    int max_ctx = 0;
+    for (int i = 0; i < B; ++i) max_ctx = std::max(max_ctx, p->h_lens[host_seq_ids[i]] + 1);
+    const size_t need = carve(m, nullptr, B, max_ctx).bytes;
+    if (ws_bytes < need) return fail(SPIRAL_ERR_OOM_KV, "decode_step: workspace of %zu bytes given, %zu needed", ws_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<int32_t> ones(B, 1);
+    rc = grow(p, host_seq_ids, ones.data(), B, s, "decode_step");
+    if (rc) return rc;
+    Workspace w = carve(m, (char*)dev_ws, B, max_ctx);
+    rc = upload_ids(p, w, dev_ws, host_seq_ids, B, s);
+    if (rc) return rc;
+    for (int i = 0; i < B; ++i) p->h_lens[host_seq_ids[i]] += 1;
+
+    EmbedArgs e = {dev_in_tokens, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h, w.seq_ids, p->d_lens,
+                   w.row_seq, w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps, 1};
+    HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
+    StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
+    return run_layers(c);
+}
+
+// ---------------------------------------------------------------------------------------------
+// sampling
+// ---------------------------------------------------------------------------------------------
+static uint64_t mix64_host(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+extern "C" int spiral_sample(const float* dev_logits, int B, int V, float temperature, uint64_t seed,
+                             const int32_t* host_seq_ids, const int32_t* host_steps, const float* dev_noise,
+                             int32_t* dev_out_tokens, void* stream) {
+    if (!dev_logits || !dev_out_tokens) return fail(SPIRAL_ERR_INVALID_ARG, "sample: null logits or output");
+    if (B < 1 || B > SPIRAL_MAX_BATCH || V < 1) return fail(SPIRAL_ERR_INVALID_ARG, "sample: bad B=%d or V=%d", B, V);
+    if (!(temperature >= 0.f) || !std::isfinite(temperature)) return fail(SPIRAL_ERR_INVALID_ARG, "sample: temperature must be finite and >= 0");
+    std::vector<uint64_t> keys(B, 0);
+    if (temperature > 0.f && !dev_noise) {
+        if (!host_seq_ids || !host_steps) return fail(SPIRAL_ERR_INVALID_ARG, "sample: seq ids and steps are needed to generate noise");
+        const uint64_t k0 = mix64_host(seed ^ 0x9E3779B97F4A7C15ull);
+        for (int i = 0; i < B; ++i) {
+            if (host_seq_ids[i] < 0 || host_steps[i] < 0) return fail(SPIRAL_ERR_INVALID_ARG, "sample: negative seq id or step");
+            keys[i] = mix64_host(k0 + (((uint64_t)(uint32_t)host_seq_ids[i] << 32) | (uint64_t)(uint32_t)host_steps[i]));
+        }
+    }
+    HIP_TRY(launch_sample(dev_logits, B, V, temperature, keys.data(), temperature > 0.f ? dev_noise : nullptr,
+                          dev_out_tokens, (hipStream_t)stream));
+    return SPIRAL_OK;
+}

@@ -1,0 +1,156 @@
+// Internal declarations shared by the host API and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "spiral.h"
+
+namespace spiral {
+
+// ---------------------------------------------------------------------------------------------
+// Activation storage between kernels.
+//   fp32-weight models: fp32 activations, plain FMA GEMMs.
+//   bf16-weight models: 16-bit activations feeding MFMA.  With SPIRAL_ACT_F16 the activations are
+//   IEEE half and the bf16 weights are widened to half in registers (exact for every bf16 value
+//   whose magnitude is in half's normal range); otherwise activations are bf16.
+// ---------------------------------------------------------------------------------------------
+#ifndef SPIRAL_ACT_F16
+#define SPIRAL_ACT_F16 1
+#endif
+
+constexpr int kPageTokens = 16;
+constexpr int kMaxGroup = 16;          // q heads per kv head handled by one attention tile
+constexpr int kUploadInts = 256;       // ints carried by value in one upload launch
+
+struct IntChunk { int32_t v[kUploadInts]; };
+struct PairChunk { int32_t idx[kUploadInts / 2]; int32_t val[kUploadInts / 2]; };
+struct KeyChunk { uint64_t key[128]; };
+struct RopeFreq { double inv_freq[64]; };   // theta^(-2j/hd), j < hd/2 <= 64
+
+// GEMM: out[m][n] = sum_k A[m][k] * W[n][k]; W is up to three row blocks stacked along n
+// (q|k|v) or, for the SwiGLU epilogue, the gate and up matrices addressed by the same row.
+enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_SWIGLU = 1 };
+
+struct GemmArgs {
+    const void* A;        // activations [M][K] (act type)
+    const void* w[3];     // weight row blocks, [rows][K]
+    int32_t rows[3];      // rows in each block
+    int32_t M, N, K;      // N = total output columns (SwiGLU: ffn width)
+    void* out;            // STORE_F32: fp32 [splits][M][N]; SWIGLU: act [M][N]
+    int32_t splits;       // grid split of K (STORE_F32 only)
+    int32_t m_tiles;      // ceil(M / rows per tile)
+};
+
+struct AttnArgs {
+    const uint16_t* q;        // bf16 [rows][Hq][hd]
+    const uint16_t* pages;    // this layer's pages: [page][Hkv]{K[16][hd], V[hd][16]}
+    const int32_t* block_table;   // [max_seqs][max_blocks]
+    const int32_t* row_seq;   // [rows]
+    const int32_t* row_pos;   // [rows] position of the row's token
+    const int32_t* cu_rows;   // prefill: [B+1] first row of each sequence; decode: unused
+    float* part;              // decode: [rows][Hkv][chunks][G][hd + 2]
+    void* out;                // act [rows][Hq*hd]
+    int32_t n_rows, n_q_heads, n_kv_heads, max_blocks, chunk_pages, n_chunks;
+    float scale_log2e;        // log2(e) / sqrt(hd)
+};
+
+// Launchers (defined in the kernel translation units).  All enqueue on `s` and return the launch status.
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_upload(int32_t* dev_dst, const int32_t* host_src, int n, hipStream_t s);
+hipError_t launch_scatter(int32_t* dev_base, const int32_t* host_idx, const int32_t* host_val, int n, hipStream_t s);
+hipError_t launch_prefill_meta(const int32_t* cu_rows, const int32_t* base_pos, const int32_t* seq_ids, int B,
+                               int n_rows, int32_t* row_seq, int32_t* row_pos, hipStream_t s);
+
+struct EmbedArgs {
+    const int32_t* tokens;    // [rows]
+    const void* embed;        // [vocab][d]
+    const float* gain;        // [d]
+    float* x;                 // [rows][d]
+    void* h;                  // act [rows][d]
+    const int32_t* seq_ids;   // decode: [rows]; prefill: null
+    int32_t* lens;            // decode: device lengths, read then incremented
+    int32_t* row_seq;         // decode: written; prefill: read-only (already built)
+    int32_t* row_pos;
+    float2* rope;             // [rows][hd/2] (cos, sin)
+    int32_t n_rows, d, half_hd, vocab;
+    float eps;
+    int32_t decode;
+};
+hipError_t launch_embed_norm(const EmbedArgs& a, const RopeFreq& f, bool w_bf16, bool act32, hipStream_t s);
+
+struct NormArgs {
+    float* x;                 // [rows_in][d] residual, updated in place when n_part > 0
+    const float* part;        // [n_part][rows_in][d] projections to add, or null
+    const float* gain;        // [d]
+    void* h;                  // act [rows_out][d]
+    const int32_t* row_map;   // null, or [rows_out] source row of each output row
+    int32_t rows_in, rows_out, d, n_part;
+    float eps;
+};
+hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s);
+
+struct QkvPostArgs {
+    const float* qkv;         // [n_part][rows][(Hq+2Hkv)*hd]
+    const void* bq; const void* bk; const void* bv;   // weight dtype, or null
+    const float* q_gain; const float* k_gain;         // [hd] or null
+    const float2* rope;       // [rows][hd/2]
+    const int32_t* row_seq; const int32_t* row_pos;
+    const int32_t* block_table;
+    uint16_t* q;              // bf16 [rows][Hq][hd]
+    uint16_t* pages;          // this layer's pages
+    int32_t n_rows, n_part, n_q_heads, n_kv_heads, hd, max_blocks;
+    float eps;
+};
+hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s);
+
+hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hipStream_t s);
+hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s);
+hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s);
+
+hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
+                         const float* noise, int32_t* out, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {       // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {        // round to nearest even, saturating
+    f = fminf(fmaxf(f, -65504.0f), 65504.0f);
+    _Float16 h = (_Float16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ uint16_t f32_to_act16(float f) {
+#if SPIRAL_ACT_F16
+    return f32_to_f16_bits(f);
+#else
+    return f32_to_bf16_bits(f);
+#endif
+}
+
+template <bool ACT32> struct ActStore;
+template <> struct ActStore<true> {
+    typedef float type;
+    static __device__ __forceinline__ void put(void* base, size_t i, float v) { ((float*)base)[i] = v; }
+};
+template <> struct ActStore<false> {
+    typedef uint16_t type;
+    static __device__ __forceinline__ void put(void* base, size_t i, float v) { ((uint16_t*)base)[i] = f32_to_act16(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+}  // namespace spiral

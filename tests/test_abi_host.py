@@ -1,0 +1,112 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, validates arguments, and its RAE entry points match the
+oracle.  No GPU work is issued here."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.rae import RAE
+from paper_2506_24119_amd import binding as sb
+from paper_2506_24119_amd import inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sb.LIB_PATH):
+        from paper_2506_24119_amd.build import build
+        build(verbose=False)
+    return sb.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "spiral.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(spiral_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(sb.EXPORTS), declared ^ set(sb.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "gfx950" in sb.spiral_version()
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    with pytest.raises(OSError):
+        sb.load_library(str(tmp_path / "nope.so"))
+
+
+def test_rae_matches_oracle_within_1e6(lib):
+    gid, r0 = si.make_game_outcomes(3, 500, seed=7)          # TicTacToe / Kuhn Poker / Negotiation
+    h = sb.spiral_rae_create(3, 0.95)
+    ref = RAE(3, 0.95)
+    for lo in range(0, 500, 128):                            # 128 trajectories per policy step
+        adv = sb.spiral_rae_update(h, gid[lo:lo + 128], r0[lo:lo + 128])
+        want = ref.update(gid[lo:lo + 128], r0[lo:lo + 128])
+        assert np.abs(adv - want).max() <= 1e-6
+        assert np.abs(sb.spiral_rae_get(h, 3) - ref.b).max() <= 1e-6
+    # bit-identical in fact: same float64 operations in the same order
+    assert np.array_equal(sb.spiral_rae_get(h, 3), ref.b)
+    # snapshot / restore
+    snap = sb.spiral_rae_get(h, 3)
+    sb.spiral_rae_update(h, [0], [1.0])
+    sb.spiral_rae_set(h, snap)
+    assert np.array_equal(sb.spiral_rae_get(h, 3), snap)
+    sb.spiral_rae_free(h)
+
+
+def test_rae_rejects_bad_arguments_without_side_effects(lib):
+    with pytest.raises(sb.SpiralError) as e:
+        sb.spiral_rae_create(0, 0.95)
+    assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+    with pytest.raises(sb.SpiralError):
+        sb.spiral_rae_create(2, 1.5)
+    h = sb.spiral_rae_create(2, 0.95)
+    sb.spiral_rae_update(h, [0, 1], [1.0, -1.0])
+    before = sb.spiral_rae_get(h, 2)
+    for gid, r in (([0, 2], [1.0, 1.0]), ([0, -1], [1.0, 1.0]), ([0, 1], [1.0, float("nan")])):
+        with pytest.raises(sb.SpiralError) as e:
+            sb.spiral_rae_update(h, gid, r)
+        assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+        assert np.array_equal(sb.spiral_rae_get(h, 2), before)     # nothing was applied
+    assert "rae_update" in sb.spiral_last_error()
+    sb.spiral_rae_free(h)
+
+
+def test_model_load_validates_geometry(lib):
+    g = si.GEOMETRIES["tiny"]
+    n = 3 + sb.SPIRAL_LAYER_SLOTS * g.n_layers
+    fake = [0x1000 * (i + 1) for i in range(n)]                     # never dereferenced by model_load
+    for i in range(g.n_layers):
+        for slot in (4, 5, 6, 7, 8):
+            fake[3 + i * sb.SPIRAL_LAYER_SLOTS + slot] = None
+    m = sb.spiral_model_load(sb.make_config(g), fake)
+    assert sb.spiral_workspace_bytes(m, 4, 128) > 0
+    assert sb.spiral_workspace_bytes(m, 0, 128) == 0
+    assert sb.spiral_kv_pool_bytes(m, 10, 4, 8) > 10 * g.n_layers * g.n_kv_heads * 2 * 16 * g.head_dim * 2
+    sb.spiral_model_free(m)
+
+    def expect(code, **over):
+        cfg = sb.make_config(si.ModelGeometry(**{**g.__dict__, **over}))
+        with pytest.raises(sb.SpiralError) as e:
+            sb.spiral_model_load(cfg, fake)
+        assert e.value.code == code, sb.spiral_last_error()
+
+    expect(sb.SPIRAL_ERR_SHAPE, head_dim=48)
+    expect(sb.SPIRAL_ERR_SHAPE, n_q_heads=5)
+    expect(sb.SPIRAL_ERR_SHAPE, kv_block_tokens=32)
+    expect(sb.SPIRAL_ERR_INVALID_ARG, qk_norm=True)                 # q/k norm gains missing
+    expect(sb.SPIRAL_ERR_INVALID_ARG, n_layers=3)                   # pointer table too short
+    bad = list(fake)
+    bad[0] = 0x1008                                                 # misaligned embedding
+    with pytest.raises(sb.SpiralError):
+        sb.spiral_model_load(sb.make_config(g), bad)
+
+
+def test_sample_argument_checks_need_no_gpu(lib):
+    with pytest.raises(sb.SpiralError) as e:
+        sb.load_library()  # ensure loaded
+        rc = lib.spiral_sample(None, 1, 8, 1.0, 0, None, None, None, None, None)
+        sb._check(rc)
+    assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
