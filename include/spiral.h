@@ -117,6 +117,12 @@ int    spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_t bytes,
 void   spiral_kv_pool_free(spiral_kv_pool* p);
 /* Empties the listed sequences and returns their pages to the free list (in reverse order of use). */
 int    spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, int n, void* stream);
+/* Shortens the listed sequences to host_new_lens[i] tokens (0 <= new length <= current length) and
+ * returns the pages that are no longer needed; the cached K/V of the kept prefix stay valid.  Used
+ * to drop a discarded generation and continue from the kept history (e.g. replaying a turn).
+ * Errors: INVALID_ARG (bad id, duplicate, length out of range); nothing is modified then. */
+int    spiral_seq_truncate(spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_new_lens,
+                           int n, void* stream);
 /* Host-side view: tokens cached for a sequence (negative error code on a bad id); free pages. */
 int    spiral_seq_len(const spiral_kv_pool* p, int seq_id);
 int    spiral_kv_free_pages(const spiral_kv_pool* p);
@@ -157,6 +163,25 @@ int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_s
 int spiral_sample(const float* dev_logits, int B, int V, float temperature, uint64_t seed,
                   const int32_t* host_seq_ids, const int32_t* host_steps, const float* dev_noise,
                   int32_t* dev_out_tokens, void* stream);
+
+/* ---- measurement hooks (for benchmarks; not part of the method) --------------------------------
+ * Between spiral_profile_begin and spiral_profile_end every launch of the chosen kernel class made
+ * by spiral_prefill / spiral_decode_step on this model is bracketed by two HIP events on the call's
+ * stream.  spiral_profile_end waits for the last event and reports the number of launches seen and
+ * the sum of their durations in milliseconds.  At most max_launches launches are timed (further
+ * ones run untimed).  Errors: INVALID_ARG (unknown class, max_launches < 1, begin while active,
+ * end while inactive), HIP. */
+enum spiral_kernel_class {
+    SPIRAL_K_ATTN_DECODE = 0,   /* split-K paged decode attention (without the chunk merge) */
+    SPIRAL_K_ATTN_COMBINE,      /* merge of the per-chunk partial results */
+    SPIRAL_K_ATTN_PREFILL,
+    SPIRAL_K_GEMM_QKV, SPIRAL_K_GEMM_O, SPIRAL_K_GEMM_GATE_UP, SPIRAL_K_GEMM_DOWN, SPIRAL_K_GEMM_LM_HEAD,
+    SPIRAL_K_NORM,              /* embedding / residual-add + RMSNorm kernels */
+    SPIRAL_K_QKV_POST,          /* bias | q/k norm + RoPE + KV append */
+    SPIRAL_K_CLASSES
+};
+int spiral_profile_begin(spiral_model* m, int kernel_class, int max_launches);
+int spiral_profile_end(spiral_model* m, double* host_total_ms, int* host_n_launches);
 
 /* ---- role-conditioned advantage estimation (host only, float64) -------------------------------
  * Baselines b[game][role], role in {0,1}, start at 0 (Alg. 1, initialisation).  spiral_rae_update

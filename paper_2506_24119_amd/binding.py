@@ -27,7 +27,7 @@ SPIRAL_LAYER_SLOTS = 14
 EXPORTS = [
     "spiral_last_error", "spiral_version", "spiral_model_load", "spiral_model_free",
     "spiral_workspace_bytes", "spiral_kv_pool_bytes", "spiral_kv_pool_create", "spiral_kv_pool_free",
-    "spiral_seq_reset", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
+    "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
     "spiral_sample", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free",
 ]
@@ -84,6 +84,12 @@ def load_library(path: Optional[str] = None):
     lib.spiral_kv_pool_free.argtypes = [vp]
     lib.spiral_seq_reset.restype = C.c_int
     lib.spiral_seq_reset.argtypes = [vp, i32p, C.c_int, vp]
+    lib.spiral_seq_truncate.restype = C.c_int
+    lib.spiral_seq_truncate.argtypes = [vp, i32p, i32p, C.c_int, vp]
+    lib.spiral_profile_begin.restype = C.c_int
+    lib.spiral_profile_begin.argtypes = [vp, C.c_int, C.c_int]
+    lib.spiral_profile_end.restype = C.c_int
+    lib.spiral_profile_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]
     lib.spiral_seq_len.restype = C.c_int
     lib.spiral_seq_len.argtypes = [vp, C.c_int]
     lib.spiral_kv_free_pages.restype = C.c_int
@@ -194,6 +200,26 @@ def spiral_kv_pool_free(pool: int):
 def spiral_seq_reset(pool: int, seq_ids, stream=None):
     ids = _i32(seq_ids)
     _check(load_library().spiral_seq_reset(pool, _ip(ids), int(ids.shape[0]), _stream_handle(stream)))
+
+
+def spiral_seq_truncate(pool: int, seq_ids, new_lens, stream=None):
+    ids, ln = _i32(seq_ids), _i32(new_lens)
+    _check(load_library().spiral_seq_truncate(pool, _ip(ids), _ip(ln), int(ids.shape[0]), _stream_handle(stream)))
+
+
+KERNEL_CLASSES = ["attn_decode", "attn_combine", "attn_prefill", "gemm_qkv", "gemm_o", "gemm_gate_up",
+                  "gemm_down", "gemm_lm_head", "norm", "qkv_post"]
+
+
+def spiral_profile_begin(model: int, kernel_class: int, max_launches: int):
+    _check(load_library().spiral_profile_begin(model, kernel_class, max_launches))
+
+
+def spiral_profile_end(model: int):
+    """-> (total milliseconds, launches timed)"""
+    ms, n = C.c_double(0.0), C.c_int(0)
+    _check(load_library().spiral_profile_end(model, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 def spiral_seq_len(pool: int, seq_id: int) -> int:

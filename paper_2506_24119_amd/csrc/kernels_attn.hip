@@ -35,12 +35,13 @@ struct PageFrag {
 };
 
 template <int HD>
-__device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, int li, int lg) {
+__device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, int li, int lg, bool real) {
+    // !real: every lane reads the first 16 bytes of the page (a valid address, one cache line)
     const uint16_t* vp = kp + kPageTokens * HD;
 #pragma unroll
-    for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = *(const u32x4*)(kp + li * HD + ks * 32 + lg * 8);
+    for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = *(const u32x4*)(real ? kp + li * HD + ks * 32 + lg * 8 : kp);
 #pragma unroll
-    for (int mt = 0; mt < HD / 16; ++mt) f.v[mt] = *(const u32x2*)(vp + (mt * 16 + li) * kPageTokens + lg * 4);
+    for (int mt = 0; mt < HD / 16; ++mt) f.v[mt] = *(const u32x2*)(real ? vp + (mt * 16 + li) * kPageTokens + lg * 4 : kp);
 }
 
 template <int HD, bool PREFILL, bool ACT32>
@@ -50,7 +51,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     __shared__ float s_m[4][16];
     __shared__ float s_l[4][16];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // the wave index as a scalar, so that block-table look-ups are scalar loads (their own wait counter)
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int li = lane & 15, lg = lane >> 4;
     const int G = a.n_q_heads / a.n_kv_heads;
 
@@ -130,29 +132,36 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             ps += p[r];
         }
         l_run = l_run * alpha + ps;
+        const float m_prev = m_run;
         m_run = m_new;
         s16x4 pb;
         pb.x = (short)f32_to_bf16_bits(p[0]);
         pb.y = (short)f32_to_bf16_bits(p[1]);
         pb.z = (short)f32_to_bf16_bits(p[2]);
         pb.w = (short)f32_to_bf16_bits(p[3]);
+        // the running maximum settles after a few pages: rescale O only when some row's maximum moved
+        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            f32x4 o = acc[mt];
-            o.x *= alpha; o.y *= alpha; o.z *= alpha; o.w *= alpha;
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, f.v[mt]), pb, o, 0, 0, 0);
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
+            }
         }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, f.v[mt]), pb, acc[mt], 0, 0, 0);
     };
 
-    // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed
+    // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed.
+    // The prefetch is unconditional (past the end it re-reads one valid 16-byte spot) so that the
+    // compiler's wait counts let it stay in flight during the arithmetic.
     int pi = p_begin + wave;
     if (pi < p_end) {
         PageFrag<HD> cur, nxt;
-        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, li, lg);
+        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, li, lg, true);
         while (true) {
             const int pn = pi + 4;
             const bool more = pn < p_end;
-            if (more) load_page<HD>(nxt, a.pages + (size_t)bt[pn] * page_elems + head_off, li, lg);
+            load_page<HD>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, li, lg, more);
             step(cur, pi);
             if (!more) break;
             cur = nxt;
@@ -217,8 +226,11 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
 template <int HD, bool ACT32>
 static hipError_t decode_impl(const AttnArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((attn_kernel<HD, false, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    return hipGetLastError();
+}
+
+template <int HD, bool ACT32>
+static hipError_t combine_impl(const AttnArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((attn_combine_kernel<HD, ACT32>), dim3(a.n_rows, a.n_q_heads), dim3(HD), 0, s, a);
     return hipGetLastError();
 }
@@ -229,6 +241,16 @@ hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t
         case 32:  return act32 ? decode_impl<32, true>(a, s) : decode_impl<32, false>(a, s);
         case 64:  return act32 ? decode_impl<64, true>(a, s) : decode_impl<64, false>(a, s);
         case 128: return act32 ? decode_impl<128, true>(a, s) : decode_impl<128, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
+    if (a.n_rows <= 0 || a.n_chunks <= 0) return hipErrorInvalidValue;
+    switch (hd) {
+        case 32:  return act32 ? combine_impl<32, true>(a, s) : combine_impl<32, false>(a, s);
+        case 64:  return act32 ? combine_impl<64, true>(a, s) : combine_impl<64, false>(a, s);
+        case 128: return act32 ? combine_impl<128, true>(a, s) : combine_impl<128, false>(a, s);
     }
     return hipErrorInvalidValue;
 }

@@ -15,42 +15,9 @@
 // Weights are the MFMA "A" operand (rows i = output column n), activations the "B" operand
 // (columns j = batch row m), so that a lane ends up with 4 consecutive n of one m.
 #include "spiral_internal.h"
+#include "mfma_ops.h"
 
 namespace spiral {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-
-// bf16 pair -> half pair: widen each to fp32 (a shift), convert (exact for normal-range values)
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
-    const float lo = __uint_as_float(w << 16);
-    const float hi = __uint_as_float(w & 0xFFFF0000u);
-    typedef __attribute__((ext_vector_type(2))) __fp16 f16x2;
-    f16x2 h = __builtin_amdgcn_cvt_pkrtz(lo, hi);
-    return __builtin_bit_cast(uint32_t, h);
-}
-
-#if SPIRAL_ACT_F16
-// convert a weight fragment once, then reuse it for every batch tile
-__device__ __forceinline__ u32x4 prep_w(const u32x4& w) {
-    u32x4 wh;
-    wh.x = bf16x2_to_f16x2(w.x); wh.y = bf16x2_to_f16x2(w.y);
-    wh.z = bf16x2_to_f16x2(w.z); wh.w = bf16x2_to_f16x2(w.w);
-    return wh;
-}
-__device__ __forceinline__ f32x4 mma_prepped(const u32x4& w, const u32x4& a, const f32x4& c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, a), c, 0, 0, 0);
-}
-#else
-__device__ __forceinline__ u32x4 prep_w(const u32x4& w) { return w; }
-__device__ __forceinline__ f32x4 mma_prepped(const u32x4& w, const u32x4& a, const f32x4& c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0, 0, 0);
-}
-#endif
-
-__device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 
 // MT: 16-row batch tiles per workgroup (M tile = 16*MT), NT: 16-row weight tiles (BN = 16*NT).
 // For EPI_SWIGLU the first NT/2 weight tiles are gate rows and the last NT/2 the matching up rows.
@@ -278,6 +245,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hip
         return hipGetLastError();
     }
     if ((a.K & 31) || (a.N & 3)) return hipErrorInvalidValue;
+    if ((a.K & 127) == 0 && (a.N & 15) == 0) return launch_gemm_stream(a, epilogue, bn, s);
     if (epilogue == EPI_SWIGLU) {
         if (a.splits != 1) return hipErrorInvalidValue;
         return bn >= 64 ? launch_mfma_m<4, EPI_SWIGLU>(a, s) : launch_mfma_m<2, EPI_SWIGLU>(a, s);

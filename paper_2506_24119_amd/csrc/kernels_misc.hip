@@ -154,12 +154,33 @@ __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
     const int ro = blockIdx.x;
     const int ri = a.row_map ? a.row_map[ro] : ro;
     float* x = a.x + (size_t)ri * a.d;
+    const size_t pstride = (size_t)a.rows_in * a.d;
+    const float* prow = a.part + (size_t)ri * a.d;
     float ss = 0.f;
-    for (int i = threadIdx.x; i < a.d; i += 256) {
-        float v = x[i];
-        for (int p = 0; p < a.n_part; ++p) v += a.part[((size_t)p * a.rows_in + ri) * a.d + i];
-        if (a.n_part > 0) x[i] = v;
-        ss += v * v;
+    if ((a.d & 3) == 0) {
+        // 16-byte accesses; the (at most 8) partial loads of an element group are issued together
+        for (int i = threadIdx.x * 4; i < a.d; i += 1024) {
+            float4 v = *(const float4*)(x + i);
+            float4 pv[8];
+#pragma unroll
+            for (int p = 0; p < 8; ++p)
+                pv[p] = p < a.n_part ? *(const float4*)(prow + p * pstride + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int p = 0; p < 8; ++p) { v.x += pv[p].x; v.y += pv[p].y; v.z += pv[p].z; v.w += pv[p].w; }
+            for (int p = 8; p < a.n_part; ++p) {
+                const float4 q = *(const float4*)(prow + p * pstride + i);
+                v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
+            }
+            if (a.n_part > 0) *(float4*)(x + i) = v;
+            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        }
+    } else {
+        for (int i = threadIdx.x; i < a.d; i += 256) {
+            float v = x[i];
+            for (int p = 0; p < a.n_part; ++p) v += prow[p * pstride + i];
+            if (a.n_part > 0) x[i] = v;
+            ss += v * v;
+        }
     }
     ss = block_sum_256(ss, red);
     const float rs = rsqrtf(ss / (float)a.d + a.eps);

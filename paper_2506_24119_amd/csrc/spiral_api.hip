@@ -47,16 +47,23 @@ extern "C" const char* spiral_version(void) {
 // objects
 // ---------------------------------------------------------------------------------------------
 struct Tune {
-    int bn_qkv = 32, s_qkv = 2;
-    int bn_o = 32, s_o = 4;
+    int bn_qkv = 64, s_qkv = 3;
+    int bn_o = 64, s_o = 8;
     int bn_gu = 64;
-    int bn_down = 32, s_down = 4;
-    int bn_lm = 64;
+    int bn_down = 64, s_down = 8;
+    int bn_lm = 128;
     int chunk_pages = 16;
 };
 constexpr int kMaxSplit = 8;
 
+struct Profiler {
+    bool active = false;
+    int kclass = -1, used = 0;
+    std::vector<hipEvent_t> ev;       // start/stop pairs
+};
+
 struct spiral_model {
+    Profiler prof;
     spiral_model_config cfg;
     std::vector<const void*> w;
     bool w_bf16;
@@ -161,7 +168,69 @@ extern "C" int spiral_model_load(const spiral_model_config* cfg, const void* con
     return SPIRAL_OK;
 }
 
-extern "C" void spiral_model_free(spiral_model* m) { delete m; }
+static void drop_events(Profiler& p) {
+    for (hipEvent_t e : p.ev) (void)hipEventDestroy(e);
+    p.ev.clear();
+    p.active = false;
+    p.used = 0;
+}
+
+extern "C" void spiral_model_free(spiral_model* m) {
+    if (m) drop_events(m->prof);
+    delete m;
+}
+
+extern "C" int spiral_profile_begin(spiral_model* m, int kernel_class, int max_launches) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "profile_begin: null model");
+    if (kernel_class < 0 || kernel_class >= SPIRAL_K_CLASSES || max_launches < 1 || max_launches > (1 << 20))
+        return fail(SPIRAL_ERR_INVALID_ARG, "profile_begin: bad kernel class or launch count");
+    if (m->prof.active) return fail(SPIRAL_ERR_INVALID_ARG, "profile_begin: already active");
+    m->prof.ev.reserve((size_t)2 * max_launches);
+    for (int i = 0; i < 2 * max_launches; ++i) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) { drop_events(m->prof); return fail(SPIRAL_ERR_HIP, "profile_begin: %s", hipGetErrorString(rc)); }
+        m->prof.ev.push_back(e);
+    }
+    m->prof.kclass = kernel_class;
+    m->prof.used = 0;
+    m->prof.active = true;
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_profile_end(spiral_model* m, double* host_total_ms, int* host_n_launches) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "profile_end: null model");
+    if (!m->prof.active) return fail(SPIRAL_ERR_INVALID_ARG, "profile_end: not active");
+    if (!host_total_ms || !host_n_launches) return fail(SPIRAL_ERR_INVALID_ARG, "profile_end: null output");
+    double total = 0.0;
+    const int n = m->prof.used;
+    if (n > 0) {
+        hipError_t rc = hipEventSynchronize(m->prof.ev[2 * n - 1]);
+        if (rc != hipSuccess) { drop_events(m->prof); return fail(SPIRAL_ERR_HIP, "profile_end: %s", hipGetErrorString(rc)); }
+        for (int i = 0; i < n; ++i) {
+            float ms = 0.f;
+            rc = hipEventElapsedTime(&ms, m->prof.ev[2 * i], m->prof.ev[2 * i + 1]);
+            if (rc != hipSuccess) { drop_events(m->prof); return fail(SPIRAL_ERR_HIP, "profile_end: %s", hipGetErrorString(rc)); }
+            total += ms;
+        }
+    }
+    *host_total_ms = total;
+    *host_n_launches = n;
+    drop_events(m->prof);
+    return SPIRAL_OK;
+}
+
+// Runs one launch, bracketed by events when its class is being profiled.
+template <typename F>
+static hipError_t timed(spiral_model* m, int kclass, hipStream_t s, F&& launch) {
+    Profiler& p = m->prof;
+    const bool on = p.active && p.kclass == kclass && 2 * (p.used + 1) <= (int)p.ev.size();
+    if (on) { hipError_t e = hipEventRecord(p.ev[2 * p.used], s); if (e != hipSuccess) return e; }
+    hipError_t rc = launch();
+    if (rc != hipSuccess) return rc;
+    if (on) { hipError_t e = hipEventRecord(p.ev[2 * p.used + 1], s); if (e != hipSuccess) return e; ++p.used; }
+    return hipSuccess;
+}
 
 // ---------------------------------------------------------------------------------------------
 // workspace
@@ -305,6 +374,27 @@ extern "C" int spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, 
     return SPIRAL_OK;
 }
 
+extern "C" int spiral_seq_truncate(spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_new_lens,
+                                   int n, void* stream) {
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "seq_truncate: null pool");
+    if (n == 0) return SPIRAL_OK;
+    int rc = check_ids(p, host_seq_ids, n, "seq_truncate");
+    if (rc) return rc;
+    if (!host_new_lens) return fail(SPIRAL_ERR_INVALID_ARG, "seq_truncate: null lengths");
+    for (int i = 0; i < n; ++i)
+        if (host_new_lens[i] < 0 || host_new_lens[i] > p->h_lens[host_seq_ids[i]])
+            return fail(SPIRAL_ERR_INVALID_ARG, "seq_truncate: length %d outside [0, %d] for sequence %d",
+                        host_new_lens[i], p->h_lens[host_seq_ids[i]], host_seq_ids[i]);
+    HIP_TRY(launch_scatter(p->d_lens, host_seq_ids, host_new_lens, n, (hipStream_t)stream));
+    for (int i = 0; i < n; ++i) {
+        std::vector<int32_t>& pg = p->h_pages[host_seq_ids[i]];
+        const size_t keep = (size_t)(host_new_lens[i] + kPageTokens - 1) / kPageTokens;
+        while (pg.size() > keep) { p->free_list.push_back(pg.back()); pg.pop_back(); }
+        p->h_lens[host_seq_ids[i]] = host_new_lens[i];
+    }
+    return SPIRAL_OK;
+}
+
 extern "C" int spiral_seq_len(const spiral_kv_pool* p, int seq_id) {
     if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "seq_len: null pool");
     if (seq_id < 0 || seq_id >= p->max_seqs) return fail(SPIRAL_ERR_INVALID_ARG, "seq_len: id %d out of range", seq_id);
@@ -376,26 +466,27 @@ static int run_layers(StepCtx& c) {
     const int d = cfg.d_model, hd = cfg.head_dim;
     const int qw = cfg.n_q_heads * hd, kw = cfg.n_kv_heads * hd, nqkv = qw + 2 * kw;
     const bool wide = c.rows > 128 || act32;      // many row tiles already fill the GPU: no K split
-    const int s_qkv = wide ? 1 : t.s_qkv, s_o = wide ? 1 : t.s_o, s_down = wide ? 1 : t.s_down;
+    auto eff_split = [&](int s, int K) { return wide ? 1 : std::max(1, std::min(s, K / 128)); };
+    const int s_qkv = eff_split(t.s_qkv, d), s_o = eff_split(t.s_o, qw), s_down = eff_split(t.s_down, cfg.ffn_dim);
     int pending = 0;            // projection partials waiting to be added to the residual
 
     for (int l = 0; l < cfg.n_layers; ++l) {
         if (l > 0) {
             NormArgs n = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_ATTN_NORM), c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps};
-            HIP_TRY(launch_add_norm(n, act32, c.s));
+            HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(n, act32, c.s); }));
         }
         GemmArgs g = {};
         g.A = c.w.h; g.w[0] = m->lw(l, SPIRAL_W_Q); g.w[1] = m->lw(l, SPIRAL_W_K); g.w[2] = m->lw(l, SPIRAL_W_V);
         g.rows[0] = qw; g.rows[1] = kw; g.rows[2] = kw;
         g.M = c.rows; g.N = nqkv; g.K = d; g.out = c.w.qkv; g.splits = s_qkv;
-        HIP_TRY(launch_gemm(g, EPI_STORE_F32, m->w_bf16, t.bn_qkv, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, t.bn_qkv, c.s); }));
 
         uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
         QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
                           (const float*)m->lw(l, SPIRAL_W_Q_NORM), (const float*)m->lw(l, SPIRAL_W_K_NORM),
                           c.w.rope, c.w.row_seq, c.w.row_pos, c.p->d_block_table, c.w.q, pages,
                           c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps};
-        HIP_TRY(launch_qkv_post(qa, m->w_bf16, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_QKV_POST, c.s, [&] { return launch_qkv_post(qa, m->w_bf16, c.s); }));
 
         AttnArgs aa = {};
         aa.q = c.w.q; aa.pages = pages; aa.block_table = c.p->d_block_table; aa.row_seq = c.w.row_seq;
@@ -403,37 +494,41 @@ static int run_layers(StepCtx& c) {
         aa.n_rows = c.rows; aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
         aa.max_blocks = c.p->max_blocks; aa.chunk_pages = t.chunk_pages; aa.n_chunks = c.n_chunks;
         aa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
-        if (c.decode) HIP_TRY(launch_attn_decode(aa, hd, act32, c.s));
-        else HIP_TRY(launch_attn_prefill(aa, hd, c.B, c.max_new, act32, c.s));
+        if (c.decode) {
+            HIP_TRY(timed(m, SPIRAL_K_ATTN_DECODE, c.s, [&] { return launch_attn_decode(aa, hd, act32, c.s); }));
+            HIP_TRY(timed(m, SPIRAL_K_ATTN_COMBINE, c.s, [&] { return launch_attn_combine(aa, hd, act32, c.s); }));
+        } else {
+            HIP_TRY(timed(m, SPIRAL_K_ATTN_PREFILL, c.s, [&] { return launch_attn_prefill(aa, hd, c.B, c.max_new, act32, c.s); }));
+        }
 
         GemmArgs go = {};
         go.A = c.w.o; go.w[0] = m->lw(l, SPIRAL_W_O); go.rows[0] = d;
         go.M = c.rows; go.N = d; go.K = qw; go.out = c.w.proj; go.splits = s_o;
-        HIP_TRY(launch_gemm(go, EPI_STORE_F32, m->w_bf16, t.bn_o, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_O, c.s, [&] { return launch_gemm(go, EPI_STORE_F32, m->w_bf16, t.bn_o, c.s); }));
 
         NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps};
-        HIP_TRY(launch_add_norm(n2, act32, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(n2, act32, c.s); }));
 
         GemmArgs gu = {};
         gu.A = c.w.h; gu.w[0] = m->lw(l, SPIRAL_W_GATE); gu.w[1] = m->lw(l, SPIRAL_W_UP);
         gu.rows[0] = cfg.ffn_dim; gu.rows[1] = cfg.ffn_dim;
         gu.M = c.rows; gu.N = cfg.ffn_dim; gu.K = d; gu.out = c.w.mlp; gu.splits = 1;
-        HIP_TRY(launch_gemm(gu, EPI_SWIGLU, m->w_bf16, t.bn_gu, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_GATE_UP, c.s, [&] { return launch_gemm(gu, EPI_SWIGLU, m->w_bf16, t.bn_gu, c.s); }));
 
         GemmArgs gd = {};
         gd.A = c.w.mlp; gd.w[0] = m->lw(l, SPIRAL_W_DOWN); gd.rows[0] = d;
         gd.M = c.rows; gd.N = d; gd.K = cfg.ffn_dim; gd.out = c.w.proj; gd.splits = s_down;
-        HIP_TRY(launch_gemm(gd, EPI_STORE_F32, m->w_bf16, t.bn_down, c.s));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_DOWN, c.s, [&] { return launch_gemm(gd, EPI_STORE_F32, m->w_bf16, t.bn_down, c.s); }));
         pending = s_down;
     }
     // final norm on one row per sequence, then the LM head
     NormArgs nf = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.hf, c.decode ? nullptr : c.w.last_rows,
                    c.rows, c.B, d, pending, cfg.rms_eps};
-    HIP_TRY(launch_add_norm(nf, act32, c.s));
+    HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(nf, act32, c.s); }));
     GemmArgs gl = {};
     gl.A = c.w.hf; gl.w[0] = m->w[2]; gl.rows[0] = cfg.vocab;
     gl.M = c.B; gl.N = cfg.vocab; gl.K = d; gl.out = c.logits; gl.splits = 1;
-    HIP_TRY(launch_gemm(gl, EPI_STORE_F32, m->w_bf16, t.bn_lm, c.s));
+    HIP_TRY(timed(m, SPIRAL_K_GEMM_LM_HEAD, c.s, [&] { return launch_gemm(gl, EPI_STORE_F32, m->w_bf16, t.bn_lm, c.s); }));
     return SPIRAL_OK;
 }
 

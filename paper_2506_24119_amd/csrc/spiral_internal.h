@@ -106,7 +106,9 @@ struct QkvPostArgs {
 hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hipStream_t s);
+hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s);   // K % 128 == 0, N % 16 == 0
 hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s);
+hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s);
 
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
