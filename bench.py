@@ -204,8 +204,8 @@ def main():
         "metric": "generated tokens/sec on 1 MI355X (Qwen3-4B-shaped decode); % HBM roofline",
         "value": tok_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": 1e3 * dt / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 MFMA (bf16 weights, f16 activations/KV, f32 accumulate)" if "f16 MFMA" in sb.spiral_version()
-                 else "bf16",
+        "dtype": "f16 (bf16 weights widened in registers; f16 activations and KV cache; f32 accumulate)"
+                 if "f16 MFMA" in sb.spiral_version() else "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.key}: {g.name}-shaped random init, batch {B}, prompts U[{wl.prompt_lo},{wl.prompt_hi}], "
                                f"{K} decode steps, T={wl.temperature} seeded Gumbel-max sampling, 16-token pages",

@@ -163,6 +163,29 @@ def forward_full(g, weights: Dict[str, object], tokens: Sequence[int],
     return hf @ widen(weights["lm_head"], dtype).T
 
 
+def forward_full_many(g, weights: Dict[str, object], sequences: Sequence[Sequence[int]],
+                      logits_at: Sequence[Sequence[int]], dtype=np.float64, progress=None) -> List[np.ndarray]:
+    """forward_full for several independent sequences, visiting each layer once so that its weights
+    are widened once (the only difference from calling forward_full per sequence)."""
+    toks = [np.asarray(t, dtype=np.int64) for t in sequences]
+    xs = [widen(weights["embed"][t], dtype) for t in toks]
+    for li, lw in enumerate(weights["layers"]):
+        L = _Layer(lw, dtype)
+        for i, t in enumerate(toks):
+            T = t.shape[0]
+            x = xs[i]
+            h = rmsnorm(x, L.attn_norm, g.rms_eps)
+            q, k, v = _qkv(g, L, h, np.arange(T))
+            o = causal_attention(q, k, v).reshape(T, g.n_q_heads * g.head_dim)
+            x = x + o @ L.wo.T
+            xs[i] = x + _mlp(L, rmsnorm(x, L.mlp_norm, g.rms_eps))
+        if progress is not None:
+            progress(li)
+    fn = widen(weights["final_norm"], dtype)
+    lm = widen(weights["lm_head"], dtype)
+    return [rmsnorm(xs[i][np.asarray(logits_at[i], dtype=np.int64)], fn, g.rms_eps) @ lm.T for i in range(len(toks))]
+
+
 class CachedDecoder:
     """KV-cached incremental decoding of ONE sequence (contiguous cache).
 

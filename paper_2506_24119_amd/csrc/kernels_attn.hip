@@ -1,6 +1,6 @@
 // GQA attention over the paged KV cache on the gfx950 matrix cores.
 //
-// Page layout (per layer, page, kv head): K [16 tokens][hd] followed by V [hd][16 tokens], bf16.
+// Page layout (per layer, page, kv head): K [16 tokens][hd] followed by V [hd][16 tokens], 16-bit.
 // Both are the layouts the MFMA operands want with plain 16-byte / 8-byte loads from HBM:
 //   S^T[token][row] = sum_d K[token][d] * Q[row][d]     v_mfma_f32_16x16x32_bf16, A = K page (a lane
 //                     reads 8 consecutive d of one token), B = the 16 query rows held in registers;
@@ -21,12 +21,31 @@
 namespace spiral {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr float kNegBig = -1.0e30f;
+
+// q, the cached K/V and the probabilities share the 16-bit activation format (IEEE half by default:
+// with bf16's 8 significant bits the attention output alone carries ~0.4 % error per layer)
+__device__ __forceinline__ f32x4 mma_qk(const u32x4& k, const u32x4& q, const f32x4& c) {
+#if SPIRAL_ACT_F16
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, k), __builtin_bit_cast(f16x8, q), c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k), __builtin_bit_cast(bf16x8, q), c, 0, 0, 0);
+#endif
+}
+__device__ __forceinline__ f32x4 mma_pv(const u32x2& v, const u32x2& p, const f32x4& c) {
+#if SPIRAL_ACT_F16
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, v), __builtin_bit_cast(f16x4, p), c, 0, 0, 0);
+#else
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, v), __builtin_bit_cast(s16x4, p), c, 0, 0, 0);
+#endif
+}
 
 template <int HD>
 struct PageFrag {
@@ -109,8 +128,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.k[ks]),
-                                                        __builtin_bit_cast(bf16x8, qf[ks]), s, 0, 0, 0);
+            s = mma_qk(f.k[ks], qf[ks], s);
         const int t0 = pi * kPageTokens + lg * 4;
         float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
         bool ok[4];
@@ -134,11 +152,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         l_run = l_run * alpha + ps;
         const float m_prev = m_run;
         m_run = m_new;
-        s16x4 pb;
-        pb.x = (short)f32_to_bf16_bits(p[0]);
-        pb.y = (short)f32_to_bf16_bits(p[1]);
-        pb.z = (short)f32_to_bf16_bits(p[2]);
-        pb.w = (short)f32_to_bf16_bits(p[3]);
+        u32x2 pb;
+        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
+        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
         // the running maximum settles after a few pages: rescale O only when some row's maximum moved
         if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
 #pragma unroll
@@ -148,7 +164,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, f.v[mt]), pb, acc[mt], 0, 0, 0);
+            acc[mt] = mma_pv(f.v[mt], pb, acc[mt]);
     };
 
     // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed.

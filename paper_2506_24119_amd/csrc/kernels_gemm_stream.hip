@@ -1,17 +1,21 @@
 // Weight-streaming projection kernel for the decode step (K a multiple of 128).
 //
 // out[m][n] = sum_k A[m][k] * W[n][k], M <= 128 rows per tile.  Every weight byte is used once, so
-// the kernel is organised around keeping many weight loads in flight:
-//   * a workgroup owns 64 or 128 weight rows and all (<= 128) batch rows of its M tile; each of its
-//     four waves owns 16 or 32 of those weight rows outright, so there is no reduction between waves;
-//   * weights go HBM -> registers directly in MFMA operand layout (16 B per lane), PD chunks of 128 k
-//     ahead of use; they are the only deep queue of vector-memory loads in the loop;
-//   * the activations of a chunk (128 rows x 128 k, re-read from L2) are loaded cooperatively by the
-//     256 threads in the same stage, parked in LDS (row stride 272 B: conflict-free ds_read_b128
-//     for the MFMA operand pattern) and read by all four waves;
-//   * LDS is double buffered, one barrier per chunk.
+// the kernel is a stream over W; at M = 128 it also needs ~40 % of the matrix-core peak while
+// streaming, which is why it is built on v_mfma_f32_32x32x16 (on gfx950 the 16x16x32 form issues
+// at half the rate: 32 cycles for half the flops, measured).
+//   * A workgroup (4 waves) owns 32*WN weight rows and all (<= 128) batch rows of its M tile.  The
+//     waves form a WN x WM grid (WN*WM = 4): wave (wn, wm) multiplies weight rows [32 wn, 32 wn + 32)
+//     with its 1/WM share of the batch rows, so no reduction between waves is needed.
+//   * Weights go HBM -> registers directly in MFMA operand layout (lane = row l%32, 8 consecutive k at
+//     (l/32)*8: one 16-byte load per k step of 16), PD chunks of 128 k ahead of use.
+//   * The activations of a chunk (<= 128 rows x 128 k, re-read from L2) are loaded cooperatively by
+//     the 256 threads in the same pipeline stage, parked in LDS (row stride 272 B) and read by the
+//     waves as the other MFMA operand.  LDS is double buffered, one barrier per chunk.
+//   * All prefetch loads are unconditional (past the end of the K range they re-read a valid
+//     address): a branch around a load makes the compiler wait for every outstanding load.
 // A grid-level split of K (blockIdx.y) supplies enough workgroups for the narrow projections; the
-// consumer kernel adds the partial results in a fixed order.
+// consumer kernel adds the partial results in a fixed order (bit-reproducible, no float atomics).
 #include <algorithm>
 
 #include "spiral_internal.h"
@@ -19,68 +23,76 @@
 
 namespace spiral {
 
-enum { SW_NONE = 0, SW_WIDE = 1, SW_NARROW = 2 };
-// SW_WIDE:   SwiGLU, a wave owns 16 ffn columns: tile 0 = gate rows, tile 1 = up rows (NTW = 2)
-// SW_NARROW: SwiGLU, workgroup owns 32 ffn columns: waves 0,1 gate rows, waves 2,3 the up rows (NTW = 1)
+typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-template <int MT, int NTW>
+#if SPIRAL_ACT_F16
+__device__ __forceinline__ f32x16 mma32(const u32x4& w, const u32x4& a, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, a), c, 0, 0, 0);
+}
+#else
+__device__ __forceinline__ f32x16 mma32(const u32x4& w, const u32x4& a, const f32x16& c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0, 0, 0);
+}
+#endif
+
+template <int M32>
 struct Stage {
-    u32x4 a[MT];          // this thread's share of the activation chunk
-    u32x4 w[NTW][4];      // this lane's weight fragments: 4 k steps of 32
+    u32x4 a[2 * M32];     // this thread's share of the activation chunk (32*M32 rows x 256 B)
+    u32x4 w[8];           // this lane's weight fragments: 8 k steps of 16
 };
 
-template <int MT, int NTW, int MODE, int PD>
+// M32: batch tiles of 32 rows per workgroup; WN: waves along the weight rows (WM = 4 / WN along the
+// batch); SWIGLU: waves wn < WN/2 hold gate rows, the others the matching up rows.
+template <int M32, int WN, bool SWIGLU, int PD>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
+    constexpr int WM = 4 / WN;
+    constexpr int MW = M32 / WM;                    // batch tiles per wave
+    static_assert(M32 % WM == 0, "every wave needs at least one batch tile");
     constexpr int ROWB = 272;                       // LDS bytes per activation row (256 + 16 pad)
-    constexpr int BUF = 16 * MT * ROWB;
+    constexpr int BUF = 32 * M32 * ROWB;
     extern __shared__ uint4 lds_raw[];
     char* lds = (char*)lds_raw;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int li = lane & 15, lg = lane >> 4;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int wn = wave / WM, wm = wave % WM;
     const int tile_m = blockIdx.x % g.m_tiles;
     const int tile_n = blockIdx.x / g.m_tiles;
     const int split = blockIdx.y;
     const int K = g.K;
-    const int m0 = tile_m * (16 * MT);
+    const int m0 = tile_m * (32 * M32);
 
-    // ---- weight rows of this wave
-    const uint16_t* wrow[NTW];
-    int n_first;                                    // first output column (or ffn column) of this wave
-    if (MODE == SW_WIDE) {
-        n_first = tile_n * 64 + wave * 16;
-        int f = n_first + li; if (f >= g.N) f = g.N - 1;
-        wrow[0] = (const uint16_t*)g.w[0] + (size_t)f * K + lg * 8;
-        wrow[NTW - 1] = (const uint16_t*)g.w[1] + (size_t)f * K + lg * 8;
-    } else if (MODE == SW_NARROW) {
-        n_first = tile_n * 32 + (wave & 1) * 16;
-        int f = n_first + li; if (f >= g.N) f = g.N - 1;
-        wrow[0] = (const uint16_t*)(wave < 2 ? g.w[0] : g.w[1]) + (size_t)f * K + lg * 8;
+    // ---- the 32 weight rows of this wave
+    const uint16_t* wrow;
+    int n_first;                                    // first output (or ffn) column of this wave
+    if (SWIGLU) {
+        constexpr int H = WN / 2;
+        n_first = tile_n * (32 * H) + (wn % H) * 32;
+        int f = n_first + l32; if (f >= g.N) f = g.N - 1;
+        wrow = (const uint16_t*)(wn < H ? g.w[0] : g.w[1]) + (size_t)f * K + lh * 8;
     } else {
-        n_first = tile_n * (64 * NTW) + wave * (16 * NTW);
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            int n = n_first + nt * 16 + li; if (n >= g.N) n = g.N - 1;
-            const uint16_t* base; int row;
-            if (n < g.rows[0]) { base = (const uint16_t*)g.w[0]; row = n; }
-            else if (n < g.rows[0] + g.rows[1]) { base = (const uint16_t*)g.w[1]; row = n - g.rows[0]; }
-            else { base = (const uint16_t*)g.w[2]; row = n - g.rows[0] - g.rows[1]; }
-            wrow[nt] = base + (size_t)row * K + lg * 8;
-        }
+        n_first = tile_n * (32 * WN) + wn * 32;
+        int n = n_first + l32; if (n >= g.N) n = g.N - 1;
+        const uint16_t* base; int row;
+        if (n < g.rows[0]) { base = (const uint16_t*)g.w[0]; row = n; }
+        else if (n < g.rows[0] + g.rows[1]) { base = (const uint16_t*)g.w[1]; row = n - g.rows[0]; }
+        else { base = (const uint16_t*)g.w[2]; row = n - g.rows[0] - g.rows[1]; }
+        wrow = base + (size_t)row * K + lh * 8;
     }
 
-    // ---- this thread's share of an activation chunk: MT segments of 16 B (row = s / 16, column = s % 16)
-    const uint16_t* a_src[MT];
-    int a_dst[MT];
+    // ---- this thread's share of an activation chunk: 2*M32 segments of 16 B (row = s / 16, column = s % 16)
+    const uint16_t* a_src[2 * M32];
+    int a_dst[2 * M32];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) {
+    for (int i = 0; i < 2 * M32; ++i) {
         const int s = threadIdx.x + 256 * i;
         const int row = s >> 4, c16 = s & 15;
         int m = m0 + row; if (m >= g.M) m = g.M - 1;
         a_src[i] = (const uint16_t*)g.A + (size_t)m * K + c16 * 8;
         a_dst[i] = row * ROWB + c16 * 16;
     }
-    const int frag_off = li * ROWB + lg * 16;       // + mt*16*ROWB + ks*64
+    // operand read: batch row (wm*MW + t)*32 + l32, k = ks*16 + lh*8
+    const int frag_off = (wm * MW * 32 + l32) * ROWB + lh * 16;
 
     // ---- chunk range of this workgroup
     const int chunks = K >> 7;
@@ -88,42 +100,37 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
     const int ce = (int)(((long long)chunks * (split + 1)) / g.splits);
     const int NC = ce - cb;
 
-    f32x4 acc[NTW][MT];
+    f32x16 acc[MW];
 #pragma unroll
-    for (int nt = 0; nt < NTW; ++nt)
+    for (int t = 0; t < MW; ++t)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
 
-    Stage<MT, NTW> st[PD];
-    // Loads are unconditional (no branch around them) so that the compiler can count exactly how many
-    // younger loads may stay in flight at each wait; past the end of the range every lane reads the same
-    // valid 16 bytes instead, which costs one cache line.
-    const uint16_t* dummy = (const uint16_t*)g.A;
-    auto load = [&](Stage<MT, NTW>& S, int chunk) {
-        const bool ok = chunk < ce;
-        const size_t off = (size_t)chunk * 128;
+    Stage<M32> st[PD];
+    auto load = [&](Stage<M32>& S, int chunk) {
+        const int cc = chunk < ce ? chunk : ce - 1;        // past the end: re-read the last chunk (cache hit)
+        const size_t off = (size_t)cc * 128;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) S.a[i] = *(const u32x4*)(ok ? a_src[i] + off : dummy);
+        for (int i = 0; i < 2 * M32; ++i) S.a[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt)
-#pragma unroll
-            for (int ks = 0; ks < 4; ++ks) S.w[nt][ks] = *(const u32x4*)(ok ? wrow[nt] + off + ks * 32 : dummy);
+        for (int ks = 0; ks < 8; ++ks) S.w[ks] = *(const u32x4*)(wrow + off + ks * 16);
     };
-    auto iter = [&](Stage<MT, NTW>& S, int c) {
+    auto iter = [&](Stage<M32>& S, int c) {
         char* buf = lds + (c & 1) * BUF;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) *(u32x4*)(buf + a_dst[i]) = S.a[i];
+        for (int i = 0; i < 2 * M32; ++i) *(u32x4*)(buf + a_dst[i]) = S.a[i];
         __syncthreads();
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 af[MT];
+        for (int ks = 0; ks < 8; ++ks) {
+#if SPIRAL_ACT_F16
+            const u32x4 wp = prep_w(S.w[ks]);
+#else
+            const u32x4 wp = S.w[ks];
+#endif
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) af[mt] = *(const u32x4*)(buf + frag_off + mt * 16 * ROWB + ks * 64);
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const u32x4 wp = prep_w(S.w[nt][ks]);
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = mma_prepped(wp, af[mt], acc[nt][mt]);
+            for (int t = 0; t < MW; ++t) {
+                const u32x4 af = *(const u32x4*)(buf + frag_off + t * 32 * ROWB + ks * 32);
+                acc[t] = mma32(wp, af, acc[t]);
             }
         }
         load(S, cb + c + PD);
@@ -140,85 +147,85 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
     for (int i = 0; i < PD - 1; ++i)
         if (c + i < NC) iter(st[i], c + i);
 
-    // ---- epilogue: a lane holds 4 consecutive output columns (n_first + nt*16 + lg*4 ..) of batch row li
-    if (MODE == SW_NONE) {
+    // ---- epilogue.  Accumulator layout of the 32x32 tile: lane holds batch row l32 and, in registers
+    //      4b .. 4b+3, the weight rows 8b + 4*lh .. +3 (b = 0..3): four consecutive output columns each.
+    if (!SWIGLU) {
         float* out = (float*)g.out + (size_t)split * g.M * g.N;
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt)
+        for (int t = 0; t < MW; ++t) {
+            const int m = m0 + (wm * MW + t) * 32 + l32;
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int m = m0 + mt * 16 + li;
-                const int n = n_first + nt * 16 + lg * 4;
-                const f32x4 v = acc[nt][mt];
-                if (m < g.M && n < g.N) *(float4*)(out + (size_t)m * g.N + n) = make_float4(v.x, v.y, v.z, v.w);
+            for (int b = 0; b < 4; ++b) {
+                const int n = n_first + 8 * b + 4 * lh;
+                if (m < g.M && n < g.N)
+                    *(float4*)(out + (size_t)m * g.N + n) =
+                        make_float4(acc[t][4 * b], acc[t][4 * b + 1], acc[t][4 * b + 2], acc[t][4 * b + 3]);
             }
-    } else {
-        if (MODE == SW_NARROW) {
-            // waves 2,3 hand their up-projection tiles to waves 0,1 through LDS
-            __syncthreads();                        // everyone is done with the activation buffers
-            float4* x = (float4*)lds;
-            if (wave >= 2) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    const f32x4 v = acc[0][mt];
-                    x[((wave - 2) * MT + mt) * 64 + lane] = make_float4(v.x, v.y, v.z, v.w);
-                }
-            }
-            __syncthreads();
-            if (wave >= 2) return;
         }
+    } else {
+        constexpr int H = WN / 2;
+        // the up-projection waves hand their tiles to the gate waves through LDS
+        __syncthreads();                            // everyone is done with the activation buffers
+        float4* x = (float4*)lds;
+        const int pair = (wn % H) * WM + wm;        // gate wave and up wave of the same tile share this slot
+        if (wn >= H) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int m = m0 + mt * 16 + li;
-            const int f = n_first + lg * 4;
-            const f32x4 gs = acc[0][mt];
-            f32x4 us;
-            if (MODE == SW_NARROW) {
-                const float4 t = ((const float4*)lds)[(wave * MT + mt) * 64 + lane];
-                us = f32x4{t.x, t.y, t.z, t.w};
-            } else {
-                us = acc[NTW - 1][mt];
-            }
-            if (m < g.M && f < g.N) {
-                ushort4 o;
-                o.x = f32_to_act16(silu_f(gs.x) * us.x);
-                o.y = f32_to_act16(silu_f(gs.y) * us.y);
-                o.z = f32_to_act16(silu_f(gs.z) * us.z);
-                o.w = f32_to_act16(silu_f(gs.w) * us.w);
-                *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
+            for (int t = 0; t < MW; ++t)
+#pragma unroll
+                for (int b = 0; b < 4; ++b)
+                    x[((pair * MW + t) * 4 + b) * 64 + lane] =
+                        make_float4(acc[t][4 * b], acc[t][4 * b + 1], acc[t][4 * b + 2], acc[t][4 * b + 3]);
+        }
+        __syncthreads();
+        if (wn >= H) return;
+#pragma unroll
+        for (int t = 0; t < MW; ++t) {
+            const int m = m0 + (wm * MW + t) * 32 + l32;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int f = n_first + 8 * b + 4 * lh;
+                const float4 u = x[((pair * MW + t) * 4 + b) * 64 + lane];
+                if (m < g.M && f < g.N) {
+                    ushort4 o;
+                    o.x = f32_to_act16(silu_f(acc[t][4 * b]) * u.x);
+                    o.y = f32_to_act16(silu_f(acc[t][4 * b + 1]) * u.y);
+                    o.z = f32_to_act16(silu_f(acc[t][4 * b + 2]) * u.z);
+                    o.w = f32_to_act16(silu_f(acc[t][4 * b + 3]) * u.w);
+                    *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
+                }
             }
         }
     }
 }
 
-template <int MT, int NTW, int MODE, int PD>
+template <int M32, int WN, bool SWIGLU, int PD>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     GemmArgs g = a;
-    g.m_tiles = (a.M + 16 * MT - 1) / (16 * MT);
-    const int cols = MODE == SW_WIDE ? 64 : (MODE == SW_NARROW ? 32 : 64 * NTW);
+    g.m_tiles = (a.M + 32 * M32 - 1) / (32 * M32);
+    const int cols = SWIGLU ? 16 * WN : 32 * WN;
     const int n_tiles = (a.N + cols - 1) / cols;
-    size_t lds_bytes = (size_t)2 * 16 * MT * 272;
-    if (MODE == SW_NARROW) lds_bytes = std::max(lds_bytes, (size_t)2 * MT * 64 * sizeof(float4));
-    hipLaunchKernelGGL((gemm_stream_kernel<MT, NTW, MODE, PD>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
+    size_t lds_bytes = (size_t)2 * 32 * M32 * 272;
+    if (SWIGLU) lds_bytes = std::max(lds_bytes, (size_t)2 * M32 * 4 * 64 * sizeof(float4));
+    hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, SWIGLU, PD>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
                        lds_bytes, s, g);
     return hipGetLastError();
 }
 
-template <int NTW, int MODE>
-static hipError_t launch_m(const GemmArgs& a, hipStream_t s) {
-    if (a.M <= 16) return launch_one<1, NTW, MODE, 4>(a, s);
-    if (a.M <= 32) return launch_one<2, NTW, MODE, 4>(a, s);
-    if (a.M <= 64) return launch_one<4, NTW, MODE, 4>(a, s);
-    return launch_one<8, NTW, MODE, 3>(a, s);
+template <bool SWIGLU>
+static hipError_t launch_shape(const GemmArgs& a, int bn, hipStream_t s) {
+    // bn = weight rows per workgroup (128 or 64); narrower workgroups split the batch between waves
+    if (a.M <= 32) return launch_one<1, 4, SWIGLU, 4>(a, s);
+    if (a.M <= 64) return bn >= 128 ? launch_one<2, 4, SWIGLU, 3>(a, s) : launch_one<2, 2, SWIGLU, 3>(a, s);
+    return bn >= 128 ? launch_one<4, 4, SWIGLU, 2>(a, s) : launch_one<4, 2, SWIGLU, 3>(a, s);
 }
 
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s) {
     if ((a.K & 127) || (a.N & 15) || a.splits < 1 || a.splits > (a.K >> 7)) return hipErrorInvalidValue;
     if (epilogue == EPI_SWIGLU) {
         if (a.splits != 1) return hipErrorInvalidValue;
-        return bn >= 128 ? launch_m<2, SW_WIDE>(a, s) : launch_m<1, SW_NARROW>(a, s);
+        return launch_shape<true>(a, bn, s);
     }
-    return bn >= 128 ? launch_m<2, SW_NONE>(a, s) : launch_m<1, SW_NONE>(a, s);
+    return launch_shape<false>(a, bn, s);
 }
 
 }  // namespace spiral

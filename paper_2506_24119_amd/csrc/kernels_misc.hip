@@ -161,13 +161,13 @@ __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
         // 16-byte accesses; the (at most 8) partial loads of an element group are issued together
         for (int i = threadIdx.x * 4; i < a.d; i += 1024) {
             float4 v = *(const float4*)(x + i);
-            float4 pv[8];
+            float4 pv[16];
 #pragma unroll
-            for (int p = 0; p < 8; ++p)
+            for (int p = 0; p < 16; ++p)
                 pv[p] = p < a.n_part ? *(const float4*)(prow + p * pstride + i) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int p = 0; p < 8; ++p) { v.x += pv[p].x; v.y += pv[p].y; v.z += pv[p].z; v.w += pv[p].w; }
-            for (int p = 8; p < a.n_part; ++p) {
+            for (int p = 0; p < 16; ++p) { v.x += pv[p].x; v.y += pv[p].y; v.z += pv[p].z; v.w += pv[p].w; }
+            for (int p = 16; p < a.n_part; ++p) {
                 const float4 q = *(const float4*)(prow + p * pstride + i);
                 v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
             }
@@ -260,16 +260,16 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
         }
         if (is_q) {
             uint16_t* q = a.q + ((size_t)r * a.n_q_heads + head) * hd;
-            q[p] = f32_to_bf16_bits(lo);
-            q[p + half] = f32_to_bf16_bits(hi);
+            q[p] = f32_to_act16(lo);
+            q[p + half] = f32_to_act16(hi);
         } else if (is_k) {
             uint16_t* K = a.pages + page_base + (size_t)slot * hd;
-            K[p] = f32_to_bf16_bits(lo);
-            K[p + half] = f32_to_bf16_bits(hi);
+            K[p] = f32_to_act16(lo);
+            K[p + half] = f32_to_act16(hi);
         } else {
             uint16_t* V = a.pages + page_base + (size_t)kPageTokens * hd;
-            V[(size_t)p * kPageTokens + slot] = f32_to_bf16_bits(lo);
-            V[(size_t)(p + half) * kPageTokens + slot] = f32_to_bf16_bits(hi);
+            V[(size_t)p * kPageTokens + slot] = f32_to_act16(lo);
+            V[(size_t)(p + half) * kPageTokens + slot] = f32_to_act16(hi);
         }
     }
 }

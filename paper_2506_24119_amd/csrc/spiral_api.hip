@@ -37,9 +37,9 @@ extern "C" const char* spiral_last_error(void) { return g_err; }
 int spiral_set_error(int code, const char* text) { return fail(code, "%s", text); }
 extern "C" const char* spiral_version(void) {
 #if SPIRAL_ACT_F16
-    return "spiral-mi355x 0.1 (gfx950; f16 MFMA activations, bf16 weights/KV)";
+    return "spiral-mi355x 0.1 (gfx950; bf16 weights, f16 activations/KV cache, f16 MFMA, f32 accumulate)";
 #else
-    return "spiral-mi355x 0.1 (gfx950; bf16 MFMA activations, bf16 weights/KV)";
+    return "spiral-mi355x 0.1 (gfx950; bf16 weights, bf16 activations/KV cache, bf16 MFMA, f32 accumulate)";
 #endif
 }
 
@@ -47,14 +47,14 @@ extern "C" const char* spiral_version(void) {
 // objects
 // ---------------------------------------------------------------------------------------------
 struct Tune {
-    int bn_qkv = 64, s_qkv = 3;
-    int bn_o = 64, s_o = 8;
-    int bn_gu = 64;
-    int bn_down = 64, s_down = 8;
+    int bn_qkv = 128, s_qkv = 5;
+    int bn_o = 128, s_o = 12;
+    int bn_gu = 128;
+    int bn_down = 128, s_down = 12;
     int bn_lm = 128;
     int chunk_pages = 16;
 };
-constexpr int kMaxSplit = 8;
+constexpr int kMaxSplit = 16;
 
 struct Profiler {
     bool active = false;

@@ -1,0 +1,103 @@
+"""Full-size parity: the benchmark configurations, in the launch configuration bench.py times
+(full batch, ragged prompts, shuffled pages, default tuning), compared with the oracle on sampled
+sequences (the oracle needs ~8 GFLOP per token at the 4B shape, so it follows a few sequences through
+every step rather than the whole batch).  Sequences are independent, so a sampled sequence's logits
+are defined by its own tokens alone."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import decoder as od
+from oracle import sampling as osamp
+from paper_2506_24119_amd import inputs as si
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 3e-2
+MARGIN = 0.1
+
+
+def _say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def _run(workload_key, n_check, decode_steps, prefill_group_tokens=8192):
+    import torch
+    from paper_2506_24119_amd import binding as sb
+
+    wl = si.WORKLOADS[workload_key]
+    g = wl.geometry
+    B = wl.batch
+    t0 = time.time()
+    w_dev = si.make_weights_torch(g, wl.seed, "cuda:0")
+    prompts = si.make_prompts(g.vocab, B, wl.prompt_lo, wl.prompt_hi, wl.seed)
+    lens = np.array([len(p) for p in prompts])
+    forced = si.make_forced_tokens(g.vocab, B, decode_steps, wl.seed)
+    check = np.argsort(lens, kind="stable")[:n_check]            # the shortest prompts: cheapest for the oracle
+    final = lens + decode_steps + 1
+    blocks = (final + 15) // 16
+    n_pages = int(blocks.sum()) + 8
+    sess = sb.Session(g, w_dev, n_pages, B, int(blocks.max()), max(B, prefill_group_tokens + int(lens.max())),
+                      int(final.max()), page_order=si.make_page_order(n_pages, wl.seed))
+    ids = np.arange(B, dtype=np.int32)
+    logits = sess.new_logits(B)
+    i = 0
+    while i < B:                                                  # prefill in groups, as bench.py does
+        j, tok = i, 0
+        while j < B and (j == i or tok + len(prompts[j]) <= prefill_group_tokens):
+            tok += len(prompts[j]); j += 1
+        sess.prefill(ids[i:j], prompts[i:j], logits=logits[i:j])
+        i = j
+    out_tok = torch.empty(B, dtype=torch.int32, device="cuda:0")
+    got_logits, got_tok = [], []
+    seed = 4242
+
+    def collect(k):
+        sess.sample(logits, wl.temperature, seed, ids, np.full(B, k, dtype=np.int32), out_tok)
+        got_logits.append(logits[torch.from_numpy(check).cuda()].cpu().numpy())
+        got_tok.append(out_tok.cpu().numpy()[check])
+
+    collect(0)
+    for k in range(decode_steps):
+        sess.decode_step(ids, torch.from_numpy(np.ascontiguousarray(forced[k])).cuda(), logits)
+        collect(k + 1)
+    torch.cuda.synchronize()
+    _say(f"[{workload_key}] GPU side done in {time.time() - t0:.1f}s; oracle on sequences {check.tolist()} "
+         f"(prompt lengths {lens[check].tolist()})")
+
+    w_host = si.weights_to_host_numpy(w_dev)
+    seqs = [np.concatenate([prompts[b], forced[:, b]]) for b in check]
+    at = [np.arange(len(prompts[b]) - 1, len(prompts[b]) + decode_steps) for b in check]
+    t0 = time.time()
+    want = od.forward_full_many(g, w_host, seqs, at,
+                                progress=lambda li: _say(f"[{workload_key}] oracle layer {li + 1}/{g.n_layers} "
+                                                         f"({time.time() - t0:.0f}s)") if (li + 1) % 6 == 0 else None)
+    worst, compared, total = 0.0, 0, 0
+    for ci, b in enumerate(check):
+        got = np.stack([got_logits[k][ci] for k in range(decode_steps + 1)]).astype(np.float64)
+        ratio = np.abs(got - want[ci]).max(axis=-1) / want[ci].std(axis=-1)
+        worst = max(worst, float(ratio.max()))
+        _say(f"[{workload_key}] seq {b}: max|dlogit|/std per step = {np.array2string(ratio, precision=4)}")
+        assert ratio.max() <= LOGIT_TOL, f"{workload_key} seq {b}: max|dlogit|/std = {ratio.max():.4g} at step {int(ratio.argmax())}"
+        for k in range(decode_steps + 1):
+            noise = osamp.gumbel_noise(seed, int(b), k, g.vocab) if wl.temperature > 0 else None
+            tok, margin = osamp.sample_row(want[ci][k], wl.temperature, noise)
+            total += 1
+            if margin > MARGIN:
+                compared += 1
+                assert got_tok[k][ci] == tok, f"{workload_key} seq {b} step {k}: token {got_tok[k][ci]} vs oracle {tok} (margin {margin:.3f})"
+    _say(f"[{workload_key}] max|dlogit|/std = {worst:.3e}; {compared}/{total} sampled tokens compared and identical")
+    sess.close()
+    return worst, compared
+
+
+def test_c2_qwen3_0p6b_shape_full_batch():
+    worst, compared = _run("C2", n_check=3, decode_steps=6)
+    assert compared > 0
+
+
+def test_c3_qwen3_4b_shape_full_batch():
+    worst, compared = _run("C3", n_check=2, decode_steps=4)
+    assert compared > 0

@@ -242,6 +242,17 @@ def test_logits_at_selects_rows_and_prefix_independence():
     np.testing.assert_allclose(od.forward_full(g, w, tokens[:6])[5], full[5], rtol=1e-12, atol=1e-13)
 
 
+def test_forward_full_many_equals_per_sequence_calls():
+    g = SMALL_BIAS
+    w = si.make_weights(g, seed=9, std=0.2)
+    rng = np.random.default_rng(9)
+    seqs = [rng.integers(0, g.vocab, size=n) for n in (7, 12, 1)]
+    at = [[3, 6], [11], [0]]
+    many = od.forward_full_many(g, w, seqs, at)
+    for s_, a_, m_ in zip(seqs, at, many):
+        np.testing.assert_array_equal(m_, od.forward_full(g, w, s_, logits_at=a_))
+
+
 def test_fp32_variant_tracks_fp64():
     g = si.GEOMETRIES["tiny"]
     w = si.make_weights(g, seed=0)
