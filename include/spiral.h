@@ -105,7 +105,8 @@ size_t spiral_workspace_bytes(const spiral_model* m, int max_rows, int max_conte
  * One pool holds the K and V of every layer for up to max_seqs sequences in n_pages pages of 16
  * tokens; a sequence owns at most max_blocks_per_seq pages.  Layout inside dev_mem (all managed by
  * the library): block table int32 [max_seqs, max_blocks_per_seq], lengths int32 [max_seqs], then the
- * pages, 16-bit (IEEE half): [layer][page][kv_head]{ K [16 tokens][head_dim] , V [head_dim][16 tokens] }.
+ * pages, 16-bit (IEEE half): [layer][page][kv_head]{ K (16 tokens x head_dim), V (head_dim x 16 tokens) },
+ * each stored in the element order of the matrix-core operands (an internal layout).
  * spiral_kv_pool_bytes gives the size dev_mem must have (0 on bad arguments); dev_mem must be
  * 256-byte aligned.  host_page_order (n_pages distinct ids in [0,n_pages), or NULL for ascending)
  * is the order in which free pages are handed out.  Creation enqueues a zero fill of the pool on

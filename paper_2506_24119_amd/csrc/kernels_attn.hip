@@ -1,7 +1,7 @@
 // GQA attention over the paged KV cache on the gfx950 matrix cores.
 //
-// Page layout (per layer, page, kv head): K [16 tokens][hd] followed by V [hd][16 tokens], 16-bit.
-// Both are the layouts the MFMA operands want with plain 16-byte / 8-byte loads from HBM:
+// Page layout (per layer, page, kv head): K (16 tokens x hd) followed by V (hd x 16 tokens), 16-bit,
+// each stored in MFMA operand order (see PageFrag) so that the operands come straight from HBM:
 //   S^T[token][row] = sum_d K[token][d] * Q[row][d]     v_mfma_f32_16x16x32_bf16, A = K page (a lane
 //                     reads 8 consecutive d of one token), B = the 16 query rows held in registers;
 //   O^T[d][row]    += sum_token V^T[d][token] * P^T[token][row]   v_mfma_f32_16x16x16_bf16, A = V page
@@ -47,20 +47,26 @@ __device__ __forceinline__ f32x4 mma_pv(const u32x2& v, const u32x2& p, const f3
 #endif
 }
 
+// One (page, kv head) holds K then V, each 16 tokens x HD elements, stored in the order the MFMA
+// operand registers want them, so that every wave-wide 16-byte load reads 1 KB of consecutive memory:
+//   K element (token t, d):  (d/32)*512 + (((d%32)/8)*16 + t)*8 + d%8
+//   V element (d, token t):  (d/32)*512 + ((t/4)*16 + d%16)*8 + ((d/16)%2)*4 + t%4
 template <int HD>
 struct PageFrag {
-    u32x4 k[HD / 32];     // K: token = lane%16, d = ks*32 + (lane/16)*8 .. +8
-    u32x2 v[HD / 16];     // V^T: d = mt*16 + lane%16, tokens (lane/16)*4 .. +4
+    u32x4 k[HD / 32];     // K: lane = (d%32)/8 * 16 + token, 8 consecutive d
+    u32x4 v[HD / 32];     // V: lane = (t/4)*16 + d%16; .xy = 4 tokens of d-tile 2m, .zw = of d-tile 2m+1
 };
 
 template <int HD>
-__device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, int li, int lg, bool real) {
+__device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, int lane, bool real) {
     // !real: every lane reads the first 16 bytes of the page (a valid address, one cache line)
     const uint16_t* vp = kp + kPageTokens * HD;
+    const int off = real ? lane * 8 : 0;
+    const int step = real ? 512 : 0;
 #pragma unroll
-    for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = *(const u32x4*)(real ? kp + li * HD + ks * 32 + lg * 8 : kp);
+    for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = *(const u32x4*)(kp + ks * step + off);
 #pragma unroll
-    for (int mt = 0; mt < HD / 16; ++mt) f.v[mt] = *(const u32x2*)(real ? vp + (mt * 16 + li) * kPageTokens + lg * 4 : kp);
+    for (int mp = 0; mp < HD / 32; ++mp) f.v[mp] = *(const u32x4*)((real ? vp : kp) + mp * step + off);
 }
 
 template <int HD, bool PREFILL, bool ACT32>
@@ -164,7 +170,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
-            acc[mt] = mma_pv(f.v[mt], pb, acc[mt]);
+        {
+            const u32x4 vv = f.v[mt >> 1];
+            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
+            acc[mt] = mma_pv(vt, pb, acc[mt]);
+        }
     };
 
     // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed.
@@ -173,11 +183,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     int pi = p_begin + wave;
     if (pi < p_end) {
         PageFrag<HD> cur, nxt;
-        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, li, lg, true);
+        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, lane, true);
         while (true) {
             const int pn = pi + 4;
             const bool more = pn < p_end;
-            load_page<HD>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, li, lg, more);
+            load_page<HD>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, lane, more);
             step(cur, pi);
             if (!more) break;
             cur = nxt;

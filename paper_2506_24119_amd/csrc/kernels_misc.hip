@@ -148,6 +148,64 @@ hipError_t launch_embed_norm(const EmbedArgs& a, const RopeFreq& f, bool w_bf16,
 // ---------------------------------------------------------------------------------------------
 // residual add of the split-K projection partials + RMSNorm.  One block per output row.
 // ---------------------------------------------------------------------------------------------
+// Wide variant: d % 4 == 0 and d <= 8192.  One block of up to 1024 threads per row; a thread owns at
+// most two groups of 4 columns, issues all of their partial-sum loads at once and keeps the sums in
+// registers between the reduction and the normalised store.
+template <bool ACT32>
+__global__ __launch_bounds__(1024) void add_norm_wide_kernel(NormArgs a) {
+    __shared__ float red[16];
+    const int ro = blockIdx.x;
+    const int ri = a.row_map ? a.row_map[ro] : ro;
+    float* x = a.x + (size_t)ri * a.d;
+    const size_t pstride = (size_t)a.rows_in * a.d;
+    const float* prow = a.part + (size_t)ri * a.d;
+    const int groups = a.d >> 2;
+    float4 v[2];
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int gidx = threadIdx.x + j * blockDim.x;
+        v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (gidx < groups) {
+            const int i = gidx * 4;
+            float4 acc = *(const float4*)(x + i);
+            float4 pv[16];
+#pragma unroll
+            for (int p = 0; p < 16; ++p)
+                pv[p] = p < a.n_part ? *(const float4*)(prow + p * pstride + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int p = 0; p < 16; ++p) { acc.x += pv[p].x; acc.y += pv[p].y; acc.z += pv[p].z; acc.w += pv[p].w; }
+            for (int p = 16; p < a.n_part; ++p) {
+                const float4 q = *(const float4*)(prow + p * pstride + i);
+                acc.x += q.x; acc.y += q.y; acc.z += q.z; acc.w += q.w;
+            }
+            if (a.n_part > 0) *(float4*)(x + i) = acc;
+            v[j] = acc;
+            ss += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
+        }
+    }
+    ss = wave_sum(ss);
+    const int wave = threadIdx.x >> 6, n_waves = (blockDim.x + 63) >> 6;
+    if ((threadIdx.x & 63) == 0) red[wave] = ss;
+    __syncthreads();
+    float tot = 0.f;
+    for (int w = 0; w < n_waves; ++w) tot += red[w];
+    const float rs = rsqrtf(tot / (float)a.d + a.eps);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int gidx = threadIdx.x + j * blockDim.x;
+        if (gidx < groups) {
+            const int i = gidx * 4;
+            const float4 gn = *(const float4*)(a.gain + i);
+            const size_t o = (size_t)ro * a.d + i;
+            ActStore<ACT32>::put(a.h, o, v[j].x * rs * gn.x);
+            ActStore<ACT32>::put(a.h, o + 1, v[j].y * rs * gn.y);
+            ActStore<ACT32>::put(a.h, o + 2, v[j].z * rs * gn.z);
+            ActStore<ACT32>::put(a.h, o + 3, v[j].w * rs * gn.w);
+        }
+    }
+}
+
 template <bool ACT32>
 __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
     __shared__ float red[4];
@@ -157,30 +215,11 @@ __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
     const size_t pstride = (size_t)a.rows_in * a.d;
     const float* prow = a.part + (size_t)ri * a.d;
     float ss = 0.f;
-    if ((a.d & 3) == 0) {
-        // 16-byte accesses; the (at most 8) partial loads of an element group are issued together
-        for (int i = threadIdx.x * 4; i < a.d; i += 1024) {
-            float4 v = *(const float4*)(x + i);
-            float4 pv[16];
-#pragma unroll
-            for (int p = 0; p < 16; ++p)
-                pv[p] = p < a.n_part ? *(const float4*)(prow + p * pstride + i) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int p = 0; p < 16; ++p) { v.x += pv[p].x; v.y += pv[p].y; v.z += pv[p].z; v.w += pv[p].w; }
-            for (int p = 16; p < a.n_part; ++p) {
-                const float4 q = *(const float4*)(prow + p * pstride + i);
-                v.x += q.x; v.y += q.y; v.z += q.z; v.w += q.w;
-            }
-            if (a.n_part > 0) *(float4*)(x + i) = v;
-            ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-        }
-    } else {
-        for (int i = threadIdx.x; i < a.d; i += 256) {
-            float v = x[i];
-            for (int p = 0; p < a.n_part; ++p) v += prow[p * pstride + i];
-            if (a.n_part > 0) x[i] = v;
-            ss += v * v;
-        }
+    for (int i = threadIdx.x; i < a.d; i += 256) {
+        float v = x[i];
+        for (int p = 0; p < a.n_part; ++p) v += prow[p * pstride + i];
+        if (a.n_part > 0) x[i] = v;
+        ss += v * v;
     }
     ss = block_sum_256(ss, red);
     const float rs = rsqrtf(ss / (float)a.d + a.eps);
@@ -189,6 +228,14 @@ __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
 }
 
 hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s) {
+    if ((a.d & 3) == 0 && a.d <= 8192) {
+        int threads = ((a.d >> 2) + 63) & ~63;
+        if (threads > 1024) threads = 1024;
+        dim3 g(a.rows_out), b(threads);
+        if (act32) hipLaunchKernelGGL((add_norm_wide_kernel<true>), g, b, 0, s, a);
+        else hipLaunchKernelGGL((add_norm_wide_kernel<false>), g, b, 0, s, a);
+        return hipGetLastError();
+    }
     dim3 g(a.rows_out), b(256);
     if (act32) hipLaunchKernelGGL((add_norm_kernel<true>), g, b, 0, s, a);
     else hipLaunchKernelGGL((add_norm_kernel<false>), g, b, 0, s, a);
@@ -198,7 +245,7 @@ hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 // q/k/v post-processing: sum the projection partials, add the bias, RMSNorm each q/k head over
 // head_dim (before RoPE), rotate q/k (rotate-half pairing), store q as bf16 and append k, v to the
-// sequence's page: K row-major [slot][hd], V transposed [hd][slot].
+// sequence's page in MFMA operand order (layout in kernels_attn.hip).
 // One wave per (row, head); lane p handles the pair (p, p + hd/2).
 // ---------------------------------------------------------------------------------------------
 template <bool WBF16>
@@ -263,13 +310,17 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
             q[p] = f32_to_act16(lo);
             q[p + half] = f32_to_act16(hi);
         } else if (is_k) {
-            uint16_t* K = a.pages + page_base + (size_t)slot * hd;
-            K[p] = f32_to_act16(lo);
-            K[p + half] = f32_to_act16(hi);
+            // K element (token, d) sits at (d/32)*512 + (((d%32)/8)*16 + token)*8 + d%8
+            uint16_t* K = a.pages + page_base;
+            const int d0 = p, d1 = p + half;
+            K[(d0 >> 5) * 512 + ((((d0 & 31) >> 3) * 16 + slot) << 3) + (d0 & 7)] = f32_to_act16(lo);
+            K[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) * 16 + slot) << 3) + (d1 & 7)] = f32_to_act16(hi);
         } else {
+            // V element (d, token) sits at (d/32)*512 + ((token/4)*16 + d%16)*8 + ((d/16)%2)*4 + token%4
             uint16_t* V = a.pages + page_base + (size_t)kPageTokens * hd;
-            V[(size_t)p * kPageTokens + slot] = f32_to_act16(lo);
-            V[(size_t)(p + half) * kPageTokens + slot] = f32_to_act16(hi);
+            const int d0 = p, d1 = p + half;
+            V[(d0 >> 5) * 512 + ((((slot >> 2) * 16) + (d0 & 15)) << 3) + (((d0 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16(lo);
+            V[(d1 >> 5) * 512 + ((((slot >> 2) * 16) + (d1 & 15)) << 3) + (((d1 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16(hi);
         }
     }
 }
