@@ -120,18 +120,20 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < 2 * M32; ++i) *(u32x4*)(buf + a_dst[i]) = S.a[i];
         __syncthreads();
+        // operand reads from LDS run one k step ahead of the MFMAs that consume them
+        u32x4 af[2][MW];
+#pragma unroll
+        for (int t = 0; t < MW; ++t) af[0][t] = *(const u32x4*)(buf + frag_off + t * 32 * ROWB);
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-#if SPIRAL_ACT_F16
-            const u32x4 wp = prep_w(S.w[ks]);
-#else
-            const u32x4 wp = S.w[ks];
-#endif
+            if (ks + 1 < 8) {
 #pragma unroll
-            for (int t = 0; t < MW; ++t) {
-                const u32x4 af = *(const u32x4*)(buf + frag_off + t * 32 * ROWB + ks * 32);
-                acc[t] = mma32(wp, af, acc[t]);
+                for (int t = 0; t < MW; ++t)
+                    af[(ks + 1) & 1][t] = *(const u32x4*)(buf + frag_off + t * 32 * ROWB + (ks + 1) * 32);
             }
+            const u32x4 wp = prep_w(S.w[ks]);
+#pragma unroll
+            for (int t = 0; t < MW; ++t) acc[t] = mma32(wp, af[ks & 1][t], acc[t]);
         }
         load(S, cb + c + PD);
     };
