@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+PMC_TRAFFIC_OVER_ALGORITHMIC = 1.042      # measured ratio for the decode attention kernel (see profiles/)
 
 
 def log(*a):
@@ -137,6 +138,9 @@ def main():
     ap.add_argument("--prefill-group-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference dispatch for "
+                         "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build is single-GPU (one process, one MI355X); run with --gpus 1. "
@@ -147,6 +151,13 @@ def main():
     from paper_2506_24119_amd import inputs as si
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     log("[bench]", sb.spiral_version())
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)                    # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = si.WORKLOADS[args.workload]
     g = wl.geometry
@@ -195,7 +206,12 @@ def main():
         ms, n = sb.spiral_profile_end(sess.model)
         assert n == K * g.n_layers, (n, K * g.n_layers)
         achieved = attn_bytes / (ms * 1e-3) / 1e9
-        roofline.update({"achieved": achieved, "frac": achieved / HBM_PEAK_GBPS,
+        # HBM bytes per launch from rocprofv3 PMC (profiles/attn_decode_c3_pmc_traffic.md): FETCH_SIZE x 2.00
+        # (calibrated on plain copies) + WRITE_SIZE x 1.00 = 1.042 x the algorithmic bytes
+        roofline.update({"traffic": PMC_TRAFFIC_OVER_ALGORITHMIC * attn_bytes / n,
+                         "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on C3, copy-calibrated: "
+                                           "1.042 x algorithmic bytes (profiles/attn_decode_c3_pmc_traffic.md)",
+                         "achieved": achieved, "frac": achieved / HBM_PEAK_GBPS,
                          "avg_launch_us": 1e3 * ms / n, "launches": n,
                          "algorithmic_bytes_per_launch": attn_bytes / n})
         log(f"[bench] attention: {n} launches, avg {1e3 * ms / n:.1f} us, {achieved:.0f} GB/s")
