@@ -200,6 +200,137 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
     }
 }
 
+// Gate/up projection with the SwiGLU epilogue kept in registers.  A wave's 32 weight rows are 16
+// gate rows followed by the 16 up rows of the same ffn columns, so in the 32x32 accumulator tile a
+// lane holds gate values in registers 0..7 and the matching up values in registers 8..15: no
+// exchange between waves.  NW waves per workgroup, each with all M32 batch tiles; NW is chosen on
+// the host so that the workgroups fill the 256 compute units in one round (9728 ffn columns are
+// 608 wave tiles: 203 workgroups of 3 use every unit at most 3 tiles deep, 152 of 4 leave 104 idle).
+template <int M32, int NW, int PD>
+__global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
+    constexpr int NT = 64 * NW;
+    constexpr int ROWB = 272;
+    constexpr int BUF = 32 * M32 * ROWB;
+    constexpr int NSEG = 32 * M32 * 16;             // 16-byte segments of an activation chunk
+    constexpr int AI = (NSEG + NT - 1) / NT;
+    extern __shared__ uint4 lds_raw[];
+    char* lds = (char*)lds_raw;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, lh = lane >> 5;
+    const int tile_m = blockIdx.x % g.m_tiles;
+    const int tile_n = blockIdx.x / g.m_tiles;
+    const int K = g.K;
+    const int m0 = tile_m * (32 * M32);
+
+    const int f_first = (tile_n * NW + wave) * 16;  // first ffn column of this wave
+    int f = f_first + (l32 & 15); if (f >= g.N) f = g.N - 1;
+    const uint16_t* wrow = (const uint16_t*)(l32 < 16 ? g.w[0] : g.w[1]) + (size_t)f * K + lh * 8;
+
+    const uint16_t* a_src[AI];
+    int a_dst[AI];
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+        int sgm = threadIdx.x + NT * i; if (sgm >= NSEG) sgm = NSEG - 1;   // the tail repeats the last segment
+        const int row = sgm >> 4, c16 = sgm & 15;
+        int m = m0 + row; if (m >= g.M) m = g.M - 1;
+        a_src[i] = (const uint16_t*)g.A + (size_t)m * K + c16 * 8;
+        a_dst[i] = row * ROWB + c16 * 16;
+    }
+    const int frag_off = l32 * ROWB + lh * 16;
+    const int NC = K >> 7;
+
+    f32x16 acc[M32];
+#pragma unroll
+    for (int t = 0; t < M32; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    struct St { u32x4 a[AI]; u32x4 w[8]; };
+    St st[PD];
+    auto load = [&](St& S, int chunk) {
+        const int cc = chunk < NC ? chunk : NC - 1;
+        const size_t off = (size_t)cc * 128;
+#pragma unroll
+        for (int i = 0; i < AI; ++i) S.a[i] = *(const u32x4*)(a_src[i] + off);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) S.w[ks] = *(const u32x4*)(wrow + off + ks * 16);
+    };
+    auto iter = [&](St& S, int c) {
+        char* buf = lds + (c & 1) * BUF;
+#pragma unroll
+        for (int i = 0; i < AI; ++i) *(u32x4*)(buf + a_dst[i]) = S.a[i];
+        __syncthreads();
+        u32x4 af[2][M32];
+#pragma unroll
+        for (int t = 0; t < M32; ++t) af[0][t] = *(const u32x4*)(buf + frag_off + t * 32 * ROWB);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            if (ks + 1 < 8) {
+#pragma unroll
+                for (int t = 0; t < M32; ++t)
+                    af[(ks + 1) & 1][t] = *(const u32x4*)(buf + frag_off + t * 32 * ROWB + (ks + 1) * 32);
+            }
+            const u32x4 wp = prep_w(S.w[ks]);
+#pragma unroll
+            for (int t = 0; t < M32; ++t) acc[t] = mma32(wp, af[ks & 1][t], acc[t]);
+        }
+        load(S, c + PD);
+    };
+
+#pragma unroll
+    for (int i = 0; i < PD; ++i) load(st[i], i);
+    int c = 0;
+    for (; c + PD <= NC; c += PD) {
+#pragma unroll
+        for (int i = 0; i < PD; ++i) iter(st[i], c + i);
+    }
+#pragma unroll
+    for (int i = 0; i < PD - 1; ++i)
+        if (c + i < NC) iter(st[i], c + i);
+
+    // registers 4b..4b+3 hold tile rows 8b + 4*lh .. +3: b = 0, 1 are gate rows, b = 2, 3 the up rows 16 below
+#pragma unroll
+    for (int t = 0; t < M32; ++t) {
+        const int m = m0 + t * 32 + l32;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int fo = f_first + 8 * b + 4 * lh;
+            if (m < g.M && fo < g.N) {
+                ushort4 o;
+                o.x = f32_to_act16(silu_f(acc[t][4 * b]) * acc[t][4 * b + 8]);
+                o.y = f32_to_act16(silu_f(acc[t][4 * b + 1]) * acc[t][4 * b + 9]);
+                o.z = f32_to_act16(silu_f(acc[t][4 * b + 2]) * acc[t][4 * b + 10]);
+                o.w = f32_to_act16(silu_f(acc[t][4 * b + 3]) * acc[t][4 * b + 11]);
+                *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + fo) = o;
+            }
+        }
+    }
+}
+
+template <int M32, int NW, int PD>
+static hipError_t launch_swiglu(const GemmArgs& a, hipStream_t s) {
+    GemmArgs g = a;
+    g.m_tiles = (a.M + 32 * M32 - 1) / (32 * M32);
+    const int n_tiles = (a.N + 16 * NW - 1) / (16 * NW);
+    const size_t lds_bytes = (size_t)2 * 32 * M32 * 272;
+    hipLaunchKernelGGL((swiglu_stream_kernel<M32, NW, PD>), dim3(n_tiles * g.m_tiles), dim3(64 * NW), lds_bytes, s, g);
+    return hipGetLastError();
+}
+
+// Waves per workgroup for the gate/up kernel: the count in {4, 5, 3} (ties in this order) that needs
+// the fewest tile-deep rounds over the compute units.
+static int swiglu_waves(int N, int m_tiles) {
+    const int units = (N + 15) / 16;
+    int best = 4; long best_cost = -1;
+    for (int nw : {4, 5, 3}) {
+        const long wgs = (long)((units + nw - 1) / nw) * m_tiles;
+        const long cost = ((wgs + 255) / 256) * nw;
+        if (best_cost < 0 || cost < best_cost) { best = nw; best_cost = cost; }
+    }
+    return best;
+}
+
 template <int M32, int WN, bool SWIGLU, int PD>
 static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     GemmArgs g = a;
@@ -225,6 +356,13 @@ hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream
     if ((a.K & 127) || (a.N & 15) || a.splits < 1 || a.splits > (a.K >> 7)) return hipErrorInvalidValue;
     if (epilogue == EPI_SWIGLU) {
         if (a.splits != 1) return hipErrorInvalidValue;
+        if (a.M > 64 && bn != 64) {
+            // bn = 96 / 128 / 160 picks 3 / 4 / 5 waves, anything else the count that fills the chip best
+            const int nw = (bn == 96 || bn == 128 || bn == 160) ? bn / 32 : swiglu_waves(a.N, (a.M + 127) / 128);
+            if (nw == 3) return launch_swiglu<4, 3, 2>(a, s);
+            if (nw == 5) return launch_swiglu<4, 5, 2>(a, s);
+            return launch_swiglu<4, 4, 2>(a, s);
+        }
         return launch_shape<true>(a, bn, s);
     }
     return launch_shape<false>(a, bn, s);

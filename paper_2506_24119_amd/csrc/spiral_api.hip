@@ -49,7 +49,7 @@ extern "C" const char* spiral_version(void) {
 struct Tune {
     int bn_qkv = 128, s_qkv = 5;
     int bn_o = 128, s_o = 12;
-    int bn_gu = 128;
+    int bn_gu = 0;                 // 0: waves per workgroup chosen from the shape
     int bn_down = 128, s_down = 12;
     int bn_lm = 128;
     int chunk_pages = 16;
