@@ -101,3 +101,17 @@ def test_c2_qwen3_0p6b_shape_full_batch():
 def test_c3_qwen3_4b_shape_full_batch():
     worst, compared = _run("C3", n_check=2, decode_steps=4)
     assert compared > 0
+
+
+def test_c5_qwen25_7b_shape_full_batch():
+    """Seven query heads per kv head (the attention tile is padded from 7 to 16 rows), QKV bias, no
+    QK-norm, untied LM head, M = 64 batch rows in every projection."""
+    worst, compared = _run("C5", n_check=2, decode_steps=4)
+    assert compared > 0
+
+
+def test_c4_long_context_full_batch():
+    """The 4B shape with prompts of 1024-4096 tokens: up to 17 attention chunks per sequence and a
+    48 GB page pool behind the shuffled block table."""
+    worst, compared = _run("C4", n_check=1, decode_steps=3)
+    assert compared > 0
