@@ -356,12 +356,13 @@ hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream
     if ((a.K & 127) || (a.N & 15) || a.splits < 1 || a.splits > (a.K >> 7)) return hipErrorInvalidValue;
     if (epilogue == EPI_SWIGLU) {
         if (a.splits != 1) return hipErrorInvalidValue;
-        if (a.M > 64 && bn != 64) {
+        if (bn != 64) {
             // bn = 96 / 128 / 160 picks 3 / 4 / 5 waves, anything else the count that fills the chip best
-            const int nw = (bn == 96 || bn == 128 || bn == 160) ? bn / 32 : swiglu_waves(a.N, (a.M + 127) / 128);
-            if (nw == 3) return launch_swiglu<4, 3, 2>(a, s);
-            if (nw == 5) return launch_swiglu<4, 5, 2>(a, s);
-            return launch_swiglu<4, 4, 2>(a, s);
+            const int rows_wg = a.M <= 32 ? 32 : a.M <= 64 ? 64 : 128;
+            const int nw = (bn == 96 || bn == 128 || bn == 160) ? bn / 32 : swiglu_waves(a.N, (a.M + rows_wg - 1) / rows_wg);
+            if (a.M <= 32) return nw == 3 ? launch_swiglu<1, 3, 4>(a, s) : nw == 5 ? launch_swiglu<1, 5, 4>(a, s) : launch_swiglu<1, 4, 4>(a, s);
+            if (a.M <= 64) return nw == 3 ? launch_swiglu<2, 3, 3>(a, s) : nw == 5 ? launch_swiglu<2, 5, 2>(a, s) : launch_swiglu<2, 4, 3>(a, s);
+            return nw == 3 ? launch_swiglu<4, 3, 2>(a, s) : nw == 5 ? launch_swiglu<4, 5, 2>(a, s) : launch_swiglu<4, 4, 2>(a, s);
         }
         return launch_shape<true>(a, bn, s);
     }

@@ -47,10 +47,11 @@ extern "C" const char* spiral_version(void) {
 // objects
 // ---------------------------------------------------------------------------------------------
 struct Tune {
-    int bn_qkv = 128, s_qkv = 5;
-    int bn_o = 128, s_o = 12;
+    // weight rows per workgroup and K splits of the narrow projections; 0 = chosen from the shape
+    int bn_qkv = 0, s_qkv = 0;
+    int bn_o = 0, s_o = 0;
     int bn_gu = 0;                 // 0: waves per workgroup chosen from the shape
-    int bn_down = 128, s_down = 12;
+    int bn_down = 0, s_down = 0;
     int bn_lm = 128;
     int chunk_pages = 16;
 };
@@ -114,7 +115,7 @@ static void parse_tune(Tune& t) {
         i = j + 1;
     }
     auto clampi = [](int& v, int lo, int hi) { v = v < lo ? lo : (v > hi ? hi : v); };
-    clampi(t.s_qkv, 1, kMaxSplit); clampi(t.s_o, 1, kMaxSplit); clampi(t.s_down, 1, kMaxSplit);
+    clampi(t.s_qkv, 0, kMaxSplit); clampi(t.s_o, 0, kMaxSplit); clampi(t.s_down, 0, kMaxSplit);
     clampi(t.chunk_pages, 1, 1 << 20);
 }
 
@@ -466,8 +467,25 @@ static int run_layers(StepCtx& c) {
     const int d = cfg.d_model, hd = cfg.head_dim;
     const int qw = cfg.n_q_heads * hd, kw = cfg.n_kv_heads * hd, nqkv = qw + 2 * kw;
     const bool wide = c.rows > 128 || act32;      // many row tiles already fill the GPU: no K split
-    auto eff_split = [&](int s, int K) { return wide ? 1 : std::max(1, std::min(s, K / 128)); };
-    const int s_qkv = eff_split(t.s_qkv, d), s_o = eff_split(t.s_o, qw), s_down = eff_split(t.s_down, cfg.ffn_dim);
+    // A narrow projection is split along K until its workgroups fill the 256 compute units in one
+    // round (at least two 128-wide k chunks per split); 64-row workgroups when 128-row ones cannot.
+    struct Shape { int bn, splits; };
+    auto shape = [&](int bn, int s, int N, int K) {
+        auto fit = [&](int rows) {
+            const int tiles = (N + rows - 1) / rows;
+            return std::max(1, std::min({256 / std::max(tiles, 1), kMaxSplit, K / 256}));
+        };
+        if (bn == 0) {
+            const int t128 = (N + 127) / 128, t64 = (N + 63) / 64;
+            bn = (t128 * fit(128) < 160 && t64 * fit(64) > t128 * fit(128)) ? 64 : 128;
+        }
+        if (s == 0) s = fit(bn);
+        if (wide) s = 1;
+        return Shape{bn, std::max(1, std::min(s, K / 128))};
+    };
+    const Shape sh_qkv = shape(t.bn_qkv, t.s_qkv, nqkv, d), sh_o = shape(t.bn_o, t.s_o, d, qw),
+                sh_down = shape(t.bn_down, t.s_down, d, cfg.ffn_dim);
+    const int s_qkv = sh_qkv.splits, s_o = sh_o.splits, s_down = sh_down.splits;
     int pending = 0;            // projection partials waiting to be added to the residual
 
     for (int l = 0; l < cfg.n_layers; ++l) {
@@ -479,7 +497,7 @@ static int run_layers(StepCtx& c) {
         g.A = c.w.h; g.w[0] = m->lw(l, SPIRAL_W_Q); g.w[1] = m->lw(l, SPIRAL_W_K); g.w[2] = m->lw(l, SPIRAL_W_V);
         g.rows[0] = qw; g.rows[1] = kw; g.rows[2] = kw;
         g.M = c.rows; g.N = nqkv; g.K = d; g.out = c.w.qkv; g.splits = s_qkv;
-        HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, t.bn_qkv, c.s); }));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, sh_qkv.bn, c.s); }));
 
         uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
         QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
@@ -504,7 +522,7 @@ static int run_layers(StepCtx& c) {
         GemmArgs go = {};
         go.A = c.w.o; go.w[0] = m->lw(l, SPIRAL_W_O); go.rows[0] = d;
         go.M = c.rows; go.N = d; go.K = qw; go.out = c.w.proj; go.splits = s_o;
-        HIP_TRY(timed(m, SPIRAL_K_GEMM_O, c.s, [&] { return launch_gemm(go, EPI_STORE_F32, m->w_bf16, t.bn_o, c.s); }));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_O, c.s, [&] { return launch_gemm(go, EPI_STORE_F32, m->w_bf16, sh_o.bn, c.s); }));
 
         NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps};
         HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(n2, act32, c.s); }));
@@ -518,7 +536,7 @@ static int run_layers(StepCtx& c) {
         GemmArgs gd = {};
         gd.A = c.w.mlp; gd.w[0] = m->lw(l, SPIRAL_W_DOWN); gd.rows[0] = d;
         gd.M = c.rows; gd.N = d; gd.K = cfg.ffn_dim; gd.out = c.w.proj; gd.splits = s_down;
-        HIP_TRY(timed(m, SPIRAL_K_GEMM_DOWN, c.s, [&] { return launch_gemm(gd, EPI_STORE_F32, m->w_bf16, t.bn_down, c.s); }));
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_DOWN, c.s, [&] { return launch_gemm(gd, EPI_STORE_F32, m->w_bf16, sh_down.bn, c.s); }));
         pending = s_down;
     }
     // final norm on one row per sequence, then the LM head
