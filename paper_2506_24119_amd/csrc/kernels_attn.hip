@@ -249,6 +249,284 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
     ActStore<ACT32>::put(a.out, ((size_t)r * a.n_q_heads + h) * HD + i, O / L);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Decode attention as one balanced stream over all (row, kv head, page) units of the batch.
+//
+// The units are ordered by (row, kv head, page); row_page_start[] is the prefix sum of the rows'
+// page counts, so unit u of row r is u - row_page_start[r] * Hkv = kvh * pages(r) + page.  Workgroup
+// w owns units [w * U, (w + 1) * U): every workgroup streams the same number of pages whatever the
+// mix of sequence lengths, and a workgroup's range is cut into segments at (row, kv head)
+// boundaries.  Within a segment the four waves take pages round-robin as in attn_kernel; at the end
+// of a segment they merge through LDS and write one partial (m, l, O) into slot
+// (row, kv head, w - first workgroup of that pair).  While a wave finishes a segment its first page of
+// the next segment is already in flight and the next query rows are loaded under the merge, so the
+// page stream does not stop at segment boundaries (a workgroup per chunk pays a start-up and a
+// drain for every 16 pages: 5.2 vs 5.9 TB/s measured).
+// ---------------------------------------------------------------------------------------------
+template <int HD, bool ACT32>
+__global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
+    constexpr int KS = HD / 32, MT = HD / 16, OSTRIDE = HD + 4;
+    extern __shared__ float lds_f[];
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int Hkv = a.n_kv_heads;
+    float* s_o = lds_f;                         // [4][G][OSTRIDE]
+    float* s_m = s_o + 4 * G * OSTRIDE;         // [4][16]
+    float* s_l = s_m + 64;                      // [4][16]
+
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int U = a.units_per_wg;
+    const int32_t* rps = a.row_page_start;
+    const int T = rps[a.n_rows] * Hkv;
+    int u = blockIdx.x * U;
+    if (u >= T) return;
+    const int u_end = min(u + U, T);
+
+    // the row that holds unit u: the largest r with row_page_start[r] * Hkv <= u.  The prefix sums
+    // increase strictly, so r + 1 is the number of entries that satisfy it: the lanes test 64 entries
+    // at a time (one round of independent loads instead of a chain of dependent ones).
+    int below = 0;
+    for (int base = 0; base < a.n_rows; base += 64) {
+        const int j = min(base + lane, a.n_rows - 1);
+        const bool hit = base + lane < a.n_rows && rps[j] * Hkv <= u;
+        below += __builtin_popcountll(__builtin_amdgcn_ballot_w64(hit));
+    }
+    const int lo = __builtin_amdgcn_readfirstlane(below) - 1;
+    struct Seg { int r, kvh, p0, p1, np, rs, pos; const int32_t* bt; };
+    Seg cur;
+    cur.r = lo;
+    cur.rs = rps[lo];
+    cur.np = rps[lo + 1] - cur.rs;
+    cur.kvh = (u - cur.rs * Hkv) / cur.np;
+    cur.p0 = (u - cur.rs * Hkv) % cur.np;
+    cur.p1 = min(cur.np, cur.p0 + (u_end - u));
+    cur.pos = a.row_pos[lo];
+    cur.bt = a.block_table + (size_t)a.row_seq[lo] * a.max_blocks;
+
+    const size_t page_elems = (size_t)Hkv * (2 * kPageTokens * HD);
+    constexpr int head_elems = 2 * kPageTokens * HD;
+
+    u32x4 qf[KS];
+    auto load_q = [&](const Seg& sg) {
+        // rows >= G of the tile are padding: they read row 0's vector and are zeroed
+        const uint16_t* qp = a.q + ((size_t)sg.r * a.n_q_heads + sg.kvh * G + (li < G ? li : 0)) * HD + lg * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 v = *(const u32x4*)(qp + ks * 32);
+            qf[ks] = li < G ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+    };
+
+    f32x4 acc[MT];
+    float m_run, l_run;
+    int limit;
+    auto reset = [&](const Seg& sg) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = kNegBig; l_run = 0.f; limit = sg.pos;
+    };
+
+    auto step = [&](const PageFrag<HD>& f, int pi) {
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], qf[ks], s);
+        const int t0 = pi * kPageTokens + lg * 4;
+        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
+        bool ok[4];
+        float mx = kNegBig;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            ok[r] = (t0 + r) <= limit;
+            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        float p[4];
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
+            ps += p[r];
+        }
+        l_run = l_run * alpha + ps;
+        const float m_prev = m_run;
+        m_run = m_new;
+        u32x2 pb;
+        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
+        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
+        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 vv = f.v[mt >> 1];
+            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
+            acc[mt] = mma_pv(vt, pb, acc[mt]);
+        }
+    };
+
+    PageFrag<HD> cur_f, nxt_f;
+    bool have = cur.p0 + wave < cur.p1;         // cur_f holds (or is being loaded with) this wave's first page of `cur`
+    load_page<HD>(cur_f, a.pages + (size_t)cur.bt[have ? cur.p0 + wave : cur.p0] * page_elems + (size_t)cur.kvh * head_elems,
+                  lane, have);
+    load_q(cur);
+    reset(cur);
+
+    while (true) {
+        // ---- where the next segment starts (if this workgroup has one)
+        const int u_next = u + (cur.p1 - cur.p0);
+        const bool has_next = u_next < u_end;
+        Seg nxt = cur;
+        if (has_next) {                          // cur ended at the last page of its pair
+            if (cur.kvh + 1 < Hkv) {
+                nxt.kvh = cur.kvh + 1;
+            } else {
+                nxt.r = cur.r + 1;
+                nxt.kvh = 0;
+                nxt.rs = cur.rs + cur.np;
+                nxt.np = rps[nxt.r + 1] - nxt.rs;
+                nxt.pos = a.row_pos[nxt.r];
+                nxt.bt = a.block_table + (size_t)a.row_seq[nxt.r] * a.max_blocks;
+            }
+            nxt.p0 = 0;
+            nxt.p1 = min(nxt.np, u_end - u_next);
+        }
+        const int pn0 = nxt.p0 + wave;
+        const bool cross = has_next && pn0 < nxt.p1;
+
+        // ---- this wave's pages of the segment, the following page always in flight
+        if (have) {
+            int pi = cur.p0 + wave;
+            while (true) {
+                const int pn = pi + 4;
+                const bool more = pn < cur.p1;
+                const bool real = more || cross;
+                const int32_t* btp = more ? cur.bt : nxt.bt;
+                const int idx = more ? pn : (cross ? pn0 : nxt.p0);      // nxt.p0 is a valid entry (nxt = cur without a successor)
+                const int kv = more ? cur.kvh : nxt.kvh;
+                load_page<HD>(nxt_f, a.pages + (size_t)btp[idx] * page_elems + (size_t)kv * head_elems, lane, real);
+                step(cur_f, pi);
+                cur_f = nxt_f;
+                if (!more) break;
+                pi = pn;
+            }
+        } else if (cross) {
+            load_page<HD>(cur_f, a.pages + (size_t)nxt.bt[pn0] * page_elems + (size_t)nxt.kvh * head_elems, lane, true);
+        }
+
+        // ---- merge the four waves and write this segment's partial result
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        const float m_fin = m_run, l_fin = l_run;
+        f32x4 o_fin[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) o_fin[mt] = acc[mt];
+        if (has_next) { load_q(nxt); reset(nxt); }     // the query rows of the next segment arrive under the merge
+
+        __syncthreads();                               // the previous segment's merge has been read
+        if (lg == 0) { s_m[wave * 16 + li] = m_fin; s_l[wave * 16 + li] = l_fin; }
+        if (li < G) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+                *(float4*)&s_o[(wave * G + li) * OSTRIDE + mt * 16 + lg * 4] =
+                    make_float4(o_fin[mt].x, o_fin[mt].y, o_fin[mt].z, o_fin[mt].w);
+        }
+        __syncthreads();
+        {
+            const int pair_start = cur.rs * Hkv + cur.kvh * cur.np;
+            const int slot = blockIdx.x - pair_start / U;
+            float* dst0 = a.part + (((size_t)cur.r * Hkv + cur.kvh) * a.n_chunks + slot) * G * (HD + 2);
+            for (int e = threadIdx.x; e < G * HD; e += 256) {
+                const int j = e / HD, i = e % HD;
+                const float M = fmaxf(fmaxf(s_m[j], s_m[16 + j]), fmaxf(s_m[32 + j], s_m[48 + j]));
+                float L = 0.f, O = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const float sc = __builtin_amdgcn_exp2f(s_m[w * 16 + j] - M);
+                    L += s_l[w * 16 + j] * sc;
+                    O += s_o[(w * G + j) * OSTRIDE + i] * sc;
+                }
+                float* dst = dst0 + (size_t)j * (HD + 2);
+                dst[i] = O;
+                if (i == 0) { dst[HD] = M; dst[HD + 1] = L; }
+            }
+        }
+        if (!has_next) break;
+        u = u_next;
+        cur = nxt;
+        have = cross;
+    }
+}
+
+// merge the partial results of one (row, query head) written by attn_stream_kernel
+template <int HD, bool ACT32>
+__global__ __launch_bounds__(HD) void attn_stream_combine_kernel(AttnArgs a) {
+    const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
+    const int G = a.n_q_heads / a.n_kv_heads, Hkv = a.n_kv_heads;
+    const int kvh = h / G, j = h % G;
+    const int rs = a.row_page_start[r], np = a.row_page_start[r + 1] - rs;
+    const int first = (rs * Hkv + kvh * np) / a.units_per_wg;
+    const int last = (rs * Hkv + kvh * np + np - 1) / a.units_per_wg;
+    const int n_parts = last - first + 1;
+    const float* base = a.part + (((size_t)r * Hkv + kvh) * a.n_chunks * G + j) * (HD + 2);
+    const size_t cstride = (size_t)G * (HD + 2);
+    float M = kNegBig;
+    for (int c = 0; c < n_parts; ++c) M = fmaxf(M, base[c * cstride + HD]);
+    float L = 0.f, O = 0.f;
+    for (int c = 0; c < n_parts; ++c) {
+        const float sc = __builtin_amdgcn_exp2f(base[c * cstride + HD] - M);
+        L += base[c * cstride + HD + 1] * sc;
+        O += base[c * cstride + i] * sc;
+    }
+    ActStore<ACT32>::put(a.out, ((size_t)r * a.n_q_heads + h) * HD + i, O / L);
+}
+
+template <int HD, bool ACT32>
+static hipError_t stream_impl(const AttnArgs& a, hipStream_t s) {
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const size_t lds = (size_t)(4 * G * (HD + 4) + 128) * sizeof(float);
+    const int wgs = (a.total_units + a.units_per_wg - 1) / a.units_per_wg;
+    hipLaunchKernelGGL((attn_stream_kernel<HD, ACT32>), dim3(wgs), dim3(256), lds, s, a);
+    return hipGetLastError();
+}
+
+template <int HD, bool ACT32>
+static hipError_t stream_combine_impl(const AttnArgs& a, hipStream_t s) {
+    hipLaunchKernelGGL((attn_stream_combine_kernel<HD, ACT32>), dim3(a.n_rows, a.n_q_heads), dim3(HD), 0, s, a);
+    return hipGetLastError();
+}
+
+static bool stream_args_ok(const AttnArgs& a) {
+    // every (row, kv head) pair of max_pages pages must fit its partial slots: pages / U + 2 <= n_chunks
+    return a.n_rows > 0 && a.row_page_start && a.units_per_wg > 0 && a.total_units > 0 && a.n_chunks > 0 &&
+           a.n_q_heads / a.n_kv_heads <= kMaxGroup;
+}
+
+hipError_t launch_attn_stream(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
+    if (!stream_args_ok(a)) return hipErrorInvalidValue;
+    switch (hd) {
+        case 32:  return act32 ? stream_impl<32, true>(a, s) : stream_impl<32, false>(a, s);
+        case 64:  return act32 ? stream_impl<64, true>(a, s) : stream_impl<64, false>(a, s);
+        case 128: return act32 ? stream_impl<128, true>(a, s) : stream_impl<128, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
+    if (!stream_args_ok(a)) return hipErrorInvalidValue;
+    switch (hd) {
+        case 32:  return act32 ? stream_combine_impl<32, true>(a, s) : stream_combine_impl<32, false>(a, s);
+        case 64:  return act32 ? stream_combine_impl<64, true>(a, s) : stream_combine_impl<64, false>(a, s);
+        case 128: return act32 ? stream_combine_impl<128, true>(a, s) : stream_combine_impl<128, false>(a, s);
+    }
+    return hipErrorInvalidValue;
+}
+
 template <int HD, bool ACT32>
 static hipError_t decode_impl(const AttnArgs& a, hipStream_t s) {
     hipLaunchKernelGGL((attn_kernel<HD, false, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);

@@ -53,7 +53,9 @@ struct Tune {
     int bn_gu = 0;                 // 0: waves per workgroup chosen from the shape
     int bn_down = 0, s_down = 0;
     int bn_lm = 128;
-    int chunk_pages = 16;
+    int chunk_pages = 16;          // decode attention: pages per chunk (chunked kernel), least pages per workgroup (stream kernel)
+    int attn_stream = 1;           // 1: balanced page stream over the whole batch; 0: one workgroup per chunk
+    int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
 };
 constexpr int kMaxSplit = 16;
 
@@ -70,6 +72,7 @@ struct spiral_model {
     bool w_bf16;
     RopeFreq freq;
     Tune tune;
+    int n_cus = 256;
     const void* lw(int layer, int slot) const { return w[3 + layer * SPIRAL_LAYER_SLOTS + slot]; }
 };
 
@@ -110,6 +113,8 @@ static void parse_tune(Tune& t) {
                 else if (k == "down") { t.bn_down = a; if (n == 2) t.s_down = b; }
                 else if (k == "lm") { t.bn_lm = a; }
                 else if (k == "chunk") { t.chunk_pages = a; }
+                else if (k == "stream") { t.attn_stream = a; }
+                else if (k == "wgs") { t.attn_wgs = a; }
             }
         }
         i = j + 1;
@@ -165,6 +170,16 @@ extern "C" int spiral_model_load(const spiral_model_config* cfg, const void* con
     for (int j = 0; j < 64; ++j)
         m->freq.inv_freq[j] = j < c.head_dim / 2 ? std::pow((double)c.rope_theta, -2.0 * j / c.head_dim) : 0.0;
     parse_tune(m->tune);
+    {
+        // compute units of the current device (the stream attention kernel launches 3 workgroups on each);
+        // without a device the default stays, model_load itself touches no GPU state
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            m->n_cus = cus;
+        else
+            (void)hipGetLastError();
+    }
     *out = m;
     return SPIRAL_OK;
 }
@@ -239,7 +254,7 @@ static hipError_t timed(spiral_model* m, int kclass, hipStream_t s, F&& launch) 
 struct Workspace {
     float* x; void* h; float* qkv; uint16_t* q; void* o; float* proj; void* mlp; void* hf;
     float* attn_part; float2* rope;
-    int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows;
+    int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows, *page_start;
     size_t bytes;
 };
 
@@ -247,6 +262,9 @@ static int decode_chunks(const spiral_model* m, int max_context) {
     const int pages = (max_context + kPageTokens - 1) / kPageTokens;
     return std::max(1, (pages + m->tune.chunk_pages - 1) / m->tune.chunk_pages);
 }
+// partial-result slots per (row, kv head): the stream kernel gives a workgroup at least chunk_pages
+// units, so a pair of n pages is cut into at most n / chunk_pages + 2 pieces
+static int decode_slots(const spiral_model* m, int max_context) { return decode_chunks(m, max_context) + 2; }
 
 static Workspace carve(const spiral_model* m, char* base, int rows, int max_context) {
     const spiral_model_config& c = m->cfg;
@@ -267,6 +285,7 @@ static Workspace carve(const spiral_model* m, char* base, int rows, int max_cont
     w.cu_rows = (int32_t*)take((SPIRAL_MAX_BATCH + 1) * 4);
     w.base_pos = (int32_t*)take(SPIRAL_MAX_BATCH * 4);
     w.last_rows = (int32_t*)take(SPIRAL_MAX_BATCH * 4);
+    w.page_start = (int32_t*)take((SPIRAL_MAX_BATCH + 1) * 4);
     w.x = (float*)take(R * c.d_model * 4);
     w.h = take(R * c.d_model * act);
     w.qkv = (float*)take(split_rows * nqkv * 4);
@@ -278,7 +297,7 @@ static Workspace carve(const spiral_model* m, char* base, int rows, int max_cont
     w.rope = (float2*)take(R * (c.head_dim / 2) * 8);
     w.row_seq = (int32_t*)take(R * 4);
     w.row_pos = (int32_t*)take(R * 4);
-    w.attn_part = (float*)take(brows * c.n_kv_heads * decode_chunks(m, max_context) * G * (c.head_dim + 2) * 4);
+    w.attn_part = (float*)take(brows * c.n_kv_heads * decode_slots(m, max_context) * G * (c.head_dim + 2) * 4);
     w.bytes = off;
     return w;
 }
@@ -457,6 +476,7 @@ struct StepCtx {
     int max_new;         // prefill: longest appended run
     int n_chunks;        // decode: context chunks
     float* logits;
+    int total_units = 0, units_per_wg = 0, n_slots = 0;   // decode, stream kernel
 };
 
 static int run_layers(StepCtx& c) {
@@ -512,7 +532,12 @@ static int run_layers(StepCtx& c) {
         aa.n_rows = c.rows; aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
         aa.max_blocks = c.p->max_blocks; aa.chunk_pages = t.chunk_pages; aa.n_chunks = c.n_chunks;
         aa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
-        if (c.decode) {
+        if (c.decode && c.units_per_wg > 0) {
+            aa.row_page_start = c.w.page_start; aa.units_per_wg = c.units_per_wg; aa.total_units = c.total_units;
+            aa.n_chunks = c.n_slots;
+            HIP_TRY(timed(m, SPIRAL_K_ATTN_DECODE, c.s, [&] { return launch_attn_stream(aa, hd, act32, c.s); }));
+            HIP_TRY(timed(m, SPIRAL_K_ATTN_COMBINE, c.s, [&] { return launch_attn_stream_combine(aa, hd, act32, c.s); }));
+        } else if (c.decode) {
             HIP_TRY(timed(m, SPIRAL_K_ATTN_DECODE, c.s, [&] { return launch_attn_decode(aa, hd, act32, c.s); }));
             HIP_TRY(timed(m, SPIRAL_K_ATTN_COMBINE, c.s, [&] { return launch_attn_combine(aa, hd, act32, c.s); }));
         } else {
@@ -636,6 +661,16 @@ extern "C" int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int3
                    w.row_seq, w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps, 1};
     HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
     StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
+    if (m->tune.attn_stream) {
+        // page counts after this step's append, as a prefix sum over the rows of the call
+        std::vector<int32_t> start(B + 1, 0);
+        for (int i = 0; i < B; ++i) start[i + 1] = start[i] + (p->h_lens[host_seq_ids[i]] + kPageTokens - 1) / kPageTokens;
+        HIP_TRY(launch_upload(w.page_start, start.data(), B + 1, s));
+        const int wgs = m->tune.attn_wgs > 0 ? m->tune.attn_wgs : 3 * m->n_cus;
+        c.total_units = start[B] * m->cfg.n_kv_heads;
+        c.units_per_wg = std::max(m->tune.chunk_pages, (c.total_units + wgs - 1) / wgs);
+        c.n_slots = decode_slots(m, max_ctx);
+    }
     return run_layers(c);
 }
 

@@ -50,9 +50,11 @@ struct AttnArgs {
     const int32_t* row_seq;   // [rows]
     const int32_t* row_pos;   // [rows] position of the row's token
     const int32_t* cu_rows;   // prefill: [B+1] first row of each sequence; decode: unused
+    const int32_t* row_page_start;   // decode stream: [rows + 1] prefix sum of the rows' page counts
     float* part;              // decode: [rows][Hkv][chunks][G][hd + 2]
     void* out;                // act [rows][Hq*hd]
     int32_t n_rows, n_q_heads, n_kv_heads, max_blocks, chunk_pages, n_chunks;
+    int32_t units_per_wg, total_units;   // decode stream: (row, kv head, page) units per workgroup, and in all
     float scale_log2e;        // log2(e) / sqrt(hd)
 };
 
@@ -109,6 +111,8 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hip
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s);   // K % 128 == 0, N % 16 == 0
 hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
+hipError_t launch_attn_stream(const AttnArgs& a, int hd, bool act32, hipStream_t s);
+hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s);
 
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,

@@ -171,6 +171,31 @@ def test_long_context_spans_several_attention_chunks(sb):
     sess.close()
 
 
+@pytest.mark.parametrize("tune", ["stream=0", "stream=0,chunk=1", "stream=1,chunk=1,wgs=7", "stream=1,chunk=2,wgs=100000",
+                                  "stream=1,chunk=64,wgs=3"])
+@pytest.mark.parametrize("name", ["g4-qknorm", "g7-bias"])
+def test_decode_attention_launch_shapes(sb, name, tune, monkeypatch):
+    """The decode attention in every decomposition the library can choose: one workgroup per chunk of
+    pages, and the balanced page stream with workgroup ranges that cut (row, kv head) pairs at
+    arbitrary pages, hold many pairs, or hold one page each.  The library reads SPIRAL_TUNE when a
+    model is loaded."""
+    monkeypatch.setenv("SPIRAL_TUNE", tune)
+    g = SMALL[name]
+    w = si.make_weights(g, seed=23)
+    B, steps = 5, 18
+    prompts = si.make_prompts(g.vocab, B, 1, 90, seed=11)
+    prompts[0] = prompts[0][:1]
+    prompts[1] = np.resize(prompts[1], 15)                      # the first decode step fills the page exactly
+    prompts[2] = np.resize(prompts[2], 16)                      # the first decode step opens a new page
+    forced = si.make_forced_tokens(g.vocab, B, steps, seed=12)
+    sess = make_session(sb, g, w, n_pages=64, max_seqs=8, max_blocks=8, max_rows=512, max_context=128, page_seed=4)
+    got_logits, _ = run_teacher_forced(sb, sess, g, prompts, forced)
+    for b in range(B):
+        want = oracle_teacher_forced(g, w, prompts[b], forced[:, b])
+        assert_logits_close(got_logits[:, b], want, f"{name} [{tune}] seq {b}")
+    sess.close()
+
+
 # ------------------------------------------------------------------------------------------------
 # invariants of the path itself
 # ------------------------------------------------------------------------------------------------
