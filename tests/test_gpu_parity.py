@@ -239,6 +239,77 @@ def test_append_prefill_equals_single_prefill_and_reset_recycles_pages(sb):
     sess.close()
 
 
+def test_games_of_different_lengths_share_the_batch(sb):
+    """Self-play shape of the workload: each slot plays games of two turns (history, response, the
+    opponent's move appended to the cached history, second response); responses have different
+    lengths, so slots finish at different steps, are reset and refilled with the next game while the
+    others keep decoding, and every decode call lists only the live slots.  Every logits row the
+    library returns is checked against a full recompute of that game's token sequence."""
+    torch = _torch()
+    rng = np.random.default_rng(31)
+    g = SMALL["g4-qknorm"]
+    w = si.make_weights(g, seed=26)
+    n_slots, n_games = 4, 9
+    games = []
+    for i in range(n_games):
+        games.append({"hist": rng.integers(0, g.vocab, rng.integers(1, 40)), "resp1": rng.integers(0, g.vocab, rng.integers(1, 14)),
+                      "move": rng.integers(0, g.vocab, rng.integers(1, 20)), "resp2": rng.integers(0, g.vocab, rng.integers(1, 14))})
+    sess = make_session(sb, g, w, n_pages=40, max_seqs=n_slots, max_blocks=8, max_rows=256, max_context=128, page_seed=8)
+    free0 = sb.spiral_kv_free_pages(sess.pool)
+    # per slot: the game it plays, its phase, and the (position, logits) rows collected for the game
+    slot_game = [None] * n_slots
+    todo = list(range(n_games))
+    got = {i: [] for i in range(n_games)}
+    state = {}
+
+    def start(slot):
+        gi = todo.pop(0)
+        slot_game[slot] = gi
+        lg = sess.prefill([slot], [games[gi]["hist"]]).cpu().numpy()[0]
+        state[gi] = {"phase": 1, "k": 0, "len": len(games[gi]["hist"])}
+        got[gi].append((state[gi]["len"] - 1, lg))
+
+    for slot in range(n_slots):
+        start(slot)
+    calls = 0
+    while any(x is not None for x in slot_game):
+        live = [s_ for s_ in range(n_slots) if slot_game[s_] is not None]
+        toks = []
+        for s_ in live:
+            gi = slot_game[s_]; st = state[gi]
+            toks.append(games[gi]["resp1" if st["phase"] == 1 else "resp2"][st["k"]])
+        order = list(rng.permutation(len(live)))                      # the call may list the live slots in any order
+        ids = [live[j] for j in order]
+        tin = torch.tensor([int(toks[j]) for j in order], dtype=torch.int32, device=sess.device)
+        lg = sess.decode_step(ids, tin, sess.new_logits(len(ids))).cpu().numpy()
+        calls += 1
+        for row, s_ in enumerate(ids):
+            gi = slot_game[s_]; st = state[gi]
+            st["len"] += 1; st["k"] += 1
+            got[gi].append((st["len"] - 1, lg[row]))
+            resp = games[gi]["resp1" if st["phase"] == 1 else "resp2"]
+            if st["k"] == len(resp):
+                if st["phase"] == 1:                                   # the opponent moved: append to the cached history
+                    lgm = sess.prefill([s_], [games[gi]["move"]]).cpu().numpy()[0]
+                    st["len"] += len(games[gi]["move"]); st["phase"] = 2; st["k"] = 0
+                    got[gi].append((st["len"] - 1, lgm))
+                else:                                                  # game over: free the slot, start the next game
+                    assert sb.spiral_seq_len(sess.pool, s_) == st["len"]
+                    sb.spiral_seq_reset(sess.pool, [s_])
+                    slot_game[s_] = None
+                    if todo:
+                        start(s_)
+    assert sb.spiral_kv_free_pages(sess.pool) == free0
+    worst = 0.0
+    for gi, gm in enumerate(games):
+        seq = np.concatenate([gm["hist"], gm["resp1"], gm["move"], gm["resp2"]])
+        pos = [p_ for p_, _ in got[gi]]
+        want = od.forward_full(g, w, seq, logits_at=pos)
+        worst = max(worst, assert_logits_close(np.stack([r for _, r in got[gi]]), want, f"game {gi}"))
+    print(f"{n_games} games over {n_slots} slots in {calls} decode calls: max|dlogit|/std = {worst:.3e}")
+    sess.close()
+
+
 def test_errors_leave_state_untouched(sb):
     torch = _torch()
     g = SMALL["g1-mha"]
