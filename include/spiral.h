@@ -165,6 +165,24 @@ int spiral_sample(const float* dev_logits, int B, int V, float temperature, uint
                   const int32_t* host_seq_ids, const int32_t* host_steps, const float* dev_noise,
                   int32_t* dev_out_tokens, void* stream);
 
+/* ---- truncated sampling -----------------------------------------------------------------------
+ * The evaluation-time decode setting of the paper (appendix "Evaluation Settings": temperature 0.6,
+ * top-p 0.95); the actor's top-p = 1, top-k = -1 is the untruncated case and goes to spiral_sample.
+ *     z_v = logit_v / temperature (fp32)
+ *     top_k in (0, V): tau_k = the k-th largest z; keep z_v >= tau_k               (<= 0 or >= V: off)
+ *     top_p in (0, 1): over the top-k survivors, walk z in descending order and stop where the running
+ *                      sum of softmax(z) first reaches top_p; tau_p = that z; keep z_v >= tau_p  (1: off)
+ *     token = argmax over { z_v >= max(tau_k, tau_p) } of z_v + g_v, lowest index on ties
+ * Equal scores are kept or dropped together.  Noise g as in spiral_sample (dev_noise or generated).
+ * dev_threshold_out (fp32 [B], may be NULL) receives the threshold max(tau_k, tau_p) of each row,
+ * -inf when nothing was cut.  Running sums are 64-bit fixed point (2^-45 of the largest term), so
+ * results are bit-reproducible.  temperature == 0 is greedy decoding (top_k, top_p ignored).
+ * Errors: INVALID_ARG (as spiral_sample; top_p outside (0, 1]; threshold output with temperature 0), HIP. */
+int spiral_sample_truncated(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                            uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                            const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                            void* stream);
+
 /* ---- measurement hooks (for benchmarks; not part of the method) --------------------------------
  * Between spiral_profile_begin and spiral_profile_end every launch of the chosen kernel class made
  * by spiral_prefill / spiral_decode_step on this model is bracketed by two HIP events on the call's

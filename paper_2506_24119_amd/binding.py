@@ -28,7 +28,7 @@ EXPORTS = [
     "spiral_last_error", "spiral_version", "spiral_model_load", "spiral_model_free",
     "spiral_workspace_bytes", "spiral_kv_pool_bytes", "spiral_kv_pool_create", "spiral_kv_pool_free",
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
-    "spiral_sample", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
+    "spiral_sample", "spiral_sample_truncated", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free",
 ]
 
@@ -100,6 +100,9 @@ def load_library(path: Optional[str] = None):
     lib.spiral_decode_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, f32p, vp]
     lib.spiral_sample.restype = C.c_int
     lib.spiral_sample.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp, vp]
+    lib.spiral_sample_truncated.restype = C.c_int
+    lib.spiral_sample_truncated.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp,
+                                            vp, vp]
     lib.spiral_rae_create.restype = C.c_int
     lib.spiral_rae_create.argtypes = [C.c_int, C.c_double, C.POINTER(vp)]
     lib.spiral_rae_update.restype = C.c_int
@@ -255,6 +258,15 @@ def spiral_sample(dev_logits, B: int, V: int, temperature: float, seed: int, seq
     st = None if steps is None else _i32(steps)
     _check(load_library().spiral_sample(_ptr(dev_logits), B, V, float(temperature), C.c_uint64(seed), _ip(ids),
                                         _ip(st), _ptr(dev_noise), _ptr(dev_out_tokens), _stream_handle(stream)))
+
+
+def spiral_sample_truncated(dev_logits, B: int, V: int, temperature: float, top_k: int, top_p: float, seed: int, seq_ids,
+                            steps, dev_noise, dev_out_tokens, dev_threshold_out=None, stream=None):
+    ids = None if seq_ids is None else _i32(seq_ids)
+    st = None if steps is None else _i32(steps)
+    _check(load_library().spiral_sample_truncated(_ptr(dev_logits), B, V, C.c_float(temperature), int(top_k), C.c_float(top_p),
+                                                  C.c_uint64(seed), _ip(ids), _ip(st), _ptr(dev_noise), _ptr(dev_out_tokens),
+                                                  _ptr(dev_threshold_out), _stream_handle(stream)))
 
 
 # ------------------------------------------------------------------------- RAE (host only)

@@ -702,3 +702,29 @@ extern "C" int spiral_sample(const float* dev_logits, int B, int V, float temper
                           dev_out_tokens, (hipStream_t)stream));
     return SPIRAL_OK;
 }
+
+extern "C" int spiral_sample_truncated(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                                       uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                                       const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                                       void* stream) {
+    if (!(top_p > 0.f) || !(top_p <= 1.f)) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: top_p must be in (0, 1] (1 disables)");
+    if (!(temperature >= 0.f) || !std::isfinite(temperature)) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: temperature must be finite and >= 0");
+    if (temperature == 0.f && dev_threshold_out) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: greedy decoding has no threshold to report");
+    const bool cut = temperature > 0.f && ((top_k > 0 && top_k < V) || top_p < 1.f);
+    if (!cut && !dev_threshold_out)      // nothing is truncated: the plain sampler is the same draw
+        return spiral_sample(dev_logits, B, V, temperature, seed, host_seq_ids, host_steps, dev_noise, dev_out_tokens, stream);
+    if (!dev_logits || !dev_out_tokens) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: null logits or output");
+    if (B < 1 || B > SPIRAL_MAX_BATCH || V < 1) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: bad B=%d or V=%d", B, V);
+    std::vector<uint64_t> keys(B, 0);
+    if (!dev_noise) {
+        if (!host_seq_ids || !host_steps) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: seq ids and steps are needed to generate noise");
+        const uint64_t k0 = mix64_host(seed ^ 0x9E3779B97F4A7C15ull);
+        for (int i = 0; i < B; ++i) {
+            if (host_seq_ids[i] < 0 || host_steps[i] < 0) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: negative seq id or step");
+            keys[i] = mix64_host(k0 + (((uint64_t)(uint32_t)host_seq_ids[i] << 32) | (uint64_t)(uint32_t)host_steps[i]));
+        }
+    }
+    HIP_TRY(launch_sample_truncated(dev_logits, B, V, temperature, top_k, top_p < 1.f ? top_p : 1.f, keys.data(), dev_noise,
+                                    dev_out_tokens, dev_threshold_out, (hipStream_t)stream));
+    return SPIRAL_OK;
+}

@@ -117,6 +117,9 @@ hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bo
 
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
                          const float* noise, int32_t* out, hipStream_t s);
+hipError_t launch_sample_truncated(const float* logits, int B, int V, float temperature, int top_k, float top_p,
+                                   const uint64_t* host_keys, const float* noise, int32_t* out, float* tau_out,
+                                   hipStream_t s);
 
 // ---------------------------------------------------------------------------------------------
 // device helpers
