@@ -150,6 +150,28 @@ int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_s
                        const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes,
                        float* dev_logits, void* stream);
 
+/* ---- scoring pass (learner side) ---------------------------------------------------------------
+ * The policy update of the paper (Alg. 1, last step; policy-gradient equation of Sec. 3) weights
+ * log pi_theta(y_t | s_t) of every generated token with the RAE advantage of the player who produced it.
+ * spiral_score runs the same packed forward as spiral_prefill (tokens are appended to the listed
+ * sequences' caches, positions continue from their lengths, attention is causal over the whole history)
+ * and returns, instead of last-token logits,
+ *     dev_logp[r] = logit_r[dev_targets[r]] - logsumexp_v(logit_r[v])          fp32 [sum(host_lens)]
+ * for every packed row r, 0 where dev_targets[r] < 0 (int32 [sum(host_lens)], ids < vocab; the usual
+ * target of a row is the next token of its sequence).  The [rows, vocab] logits are never written.
+ * 16-bit weights and d_model % 128 == 0 only.  Workspace and errors as for spiral_prefill. */
+int spiral_score(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
+                 int B, const int32_t* dev_tokens_packed, const int32_t* dev_targets, void* dev_ws,
+                 size_t ws_bytes, float* dev_logp, void* stream);
+
+/* Values of the objective for n tokens (device arrays; dev_mask int32 or NULL = all tokens count):
+ *     dev_out2[0] = sum_t mask_t * min(r_t * A_t, clip(r_t, 1 - clip_eps, 1 + clip_eps) * A_t),  r_t = exp(new_t - old_t)
+ *     dev_out2[1] = sum_t mask_t * A_t * new_t                                   (the REINFORCE sum of Sec. 3)
+ * float64, fixed summation order, no normalisation by length (Sec. 3); clip_eps = 0.2 in the paper's
+ * hyper-parameter table.  Errors: INVALID_ARG, HIP. */
+int spiral_policy_objective(const float* dev_logp_new, const float* dev_logp_old, const float* dev_advantage,
+                            const int32_t* dev_mask, long long n, float clip_eps, double* dev_out2, void* stream);
+
 /* ---- sampling ---------------------------------------------------------------------------------
  * dev_out_tokens[i] = argmax_v( dev_logits[i,v] / temperature + g[i,v] ), lowest index on ties, in
  * fp32: an exact draw from softmax(logits / temperature) (Gumbel-max), the actor's untruncated

@@ -28,7 +28,7 @@ EXPORTS = [
     "spiral_last_error", "spiral_version", "spiral_model_load", "spiral_model_free",
     "spiral_workspace_bytes", "spiral_kv_pool_bytes", "spiral_kv_pool_create", "spiral_kv_pool_free",
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
-    "spiral_sample", "spiral_sample_truncated", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
+    "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free",
 ]
 
@@ -100,6 +100,10 @@ def load_library(path: Optional[str] = None):
     lib.spiral_decode_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, f32p, vp]
     lib.spiral_sample.restype = C.c_int
     lib.spiral_sample.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp, vp]
+    lib.spiral_score.restype = C.c_int
+    lib.spiral_score.argtypes = [vp, vp, i32p, i32p, C.c_int, vp, vp, vp, C.c_size_t, vp, vp]
+    lib.spiral_policy_objective.restype = C.c_int
+    lib.spiral_policy_objective.argtypes = [vp, vp, vp, vp, C.c_longlong, C.c_float, vp, vp]
     lib.spiral_sample_truncated.restype = C.c_int
     lib.spiral_sample_truncated.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp,
                                             vp, vp]
@@ -258,6 +262,18 @@ def spiral_sample(dev_logits, B: int, V: int, temperature: float, seed: int, seq
     st = None if steps is None else _i32(steps)
     _check(load_library().spiral_sample(_ptr(dev_logits), B, V, float(temperature), C.c_uint64(seed), _ip(ids),
                                         _ip(st), _ptr(dev_noise), _ptr(dev_out_tokens), _stream_handle(stream)))
+
+
+def spiral_score(model: int, pool: int, seq_ids, lens, dev_tokens_packed, dev_targets, ws, dev_logp, stream=None):
+    ids, ln = _i32(seq_ids), _i32(lens)
+    _check(load_library().spiral_score(model, pool, _ip(ids), _ip(ln), int(ids.shape[0]), _ptr(dev_tokens_packed),
+                                       _ptr(dev_targets), _ptr(ws), C.c_size_t(ws.numel() * ws.element_size()),
+                                       _ptr(dev_logp), _stream_handle(stream)))
+
+
+def spiral_policy_objective(dev_logp_new, dev_logp_old, dev_advantage, dev_mask, n: int, clip_eps: float, dev_out2, stream=None):
+    _check(load_library().spiral_policy_objective(_ptr(dev_logp_new), _ptr(dev_logp_old), _ptr(dev_advantage), _ptr(dev_mask),
+                                                  C.c_longlong(n), C.c_float(clip_eps), _ptr(dev_out2), _stream_handle(stream)))
 
 
 def spiral_sample_truncated(dev_logits, B: int, V: int, temperature: float, top_k: int, top_p: float, seed: int, seq_ids,

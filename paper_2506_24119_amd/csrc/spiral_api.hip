@@ -58,6 +58,7 @@ struct Tune {
     int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
 };
 constexpr int kMaxSplit = 16;
+constexpr int kScoreSplits = 64;       // vocabulary ranges of the scoring pass (partial log-sum-exp pairs per row)
 
 struct Profiler {
     bool active = false;
@@ -255,6 +256,7 @@ struct Workspace {
     float* x; void* h; float* qkv; uint16_t* q; void* o; float* proj; void* mlp; void* hf;
     float* attn_part; float2* rope;
     int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows, *page_start;
+    float *score_part, *score_tgt;
     size_t bytes;
 };
 
@@ -298,6 +300,8 @@ static Workspace carve(const spiral_model* m, char* base, int rows, int max_cont
     w.row_seq = (int32_t*)take(R * 4);
     w.row_pos = (int32_t*)take(R * 4);
     w.attn_part = (float*)take(brows * c.n_kv_heads * decode_slots(m, max_context) * G * (c.head_dim + 2) * 4);
+    w.score_part = (float*)take(R * kScoreSplits * 8);
+    w.score_tgt = (float*)take(R * 4);
     w.bytes = off;
     return w;
 }
@@ -477,6 +481,8 @@ struct StepCtx {
     int n_chunks;        // decode: context chunks
     float* logits;
     int total_units = 0, units_per_wg = 0, n_slots = 0;   // decode, stream kernel
+    const int32_t* score_targets = nullptr;                // scoring pass: per-row targets and output
+    float* score_out = nullptr;
 };
 
 static int run_layers(StepCtx& c) {
@@ -564,6 +570,19 @@ static int run_layers(StepCtx& c) {
         HIP_TRY(timed(m, SPIRAL_K_GEMM_DOWN, c.s, [&] { return launch_gemm(gd, EPI_STORE_F32, m->w_bf16, sh_down.bn, c.s); }));
         pending = s_down;
     }
+    if (c.score_out) {
+        // scoring pass: final norm on every row, then the LM head fused with log-softmax and the target gather
+        NormArgs na = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps};
+        HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(na, act32, c.s); }));
+        const int n_tiles = (cfg.vocab + 127) / 128;
+        ScoreArgs sa = {};
+        sa.A = c.w.h; sa.W = m->w[2]; sa.targets = c.score_targets; sa.part = c.w.score_part; sa.tgt_logit = c.w.score_tgt;
+        sa.M = c.rows; sa.V = cfg.vocab; sa.K = d;
+        sa.tiles_per_split = (n_tiles + kScoreSplits - 1) / kScoreSplits;
+        sa.n_splits = (n_tiles + sa.tiles_per_split - 1) / sa.tiles_per_split;
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_LM_HEAD, c.s, [&] { return launch_score(sa, c.score_out, c.s); }));
+        return SPIRAL_OK;
+    }
     // final norm on one row per sequence, then the LM head
     NormArgs nf = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.hf, c.decode ? nullptr : c.w.last_rows,
                    c.rows, c.B, d, pending, cfg.rms_eps};
@@ -585,12 +604,11 @@ static int check_common(spiral_model* m, spiral_kv_pool* p, const void* toks, vo
     return SPIRAL_OK;
 }
 
-extern "C" int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
-                              int B, const int32_t* dev_tokens_packed, void* dev_ws, size_t ws_bytes, float* dev_logits,
-                              void* stream) {
-    int rc = check_common(m, p, dev_tokens_packed, dev_ws, dev_logits, "prefill");
-    if (rc) return rc;
-    rc = check_ids(p, host_seq_ids, B, "prefill");
+// prefill and score share everything up to the output: last-row logits, or per-row log-probabilities
+static int prefill_or_score(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
+                            int B, const int32_t* dev_tokens_packed, void* dev_ws, size_t ws_bytes, float* dev_logits,
+                            const int32_t* dev_targets, float* dev_logp, void* stream) {
+    int rc = check_ids(p, host_seq_ids, B, "prefill");
     if (rc) return rc;
     if (!host_lens) return fail(SPIRAL_ERR_INVALID_ARG, "prefill: null lengths");
     long long rows = 0;
@@ -634,7 +652,36 @@ extern "C" int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t*
                    m->cfg.rms_eps, 0};
     HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
     StepCtx c = {m, p, w, s, (int)rows, B, false, max_new, 1, dev_logits};
+    c.score_targets = dev_targets;
+    c.score_out = dev_logp;
     return run_layers(c);
+}
+
+extern "C" int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
+                              int B, const int32_t* dev_tokens_packed, void* dev_ws, size_t ws_bytes, float* dev_logits,
+                              void* stream) {
+    int rc = check_common(m, p, dev_tokens_packed, dev_ws, dev_logits, "prefill");
+    if (rc) return rc;
+    return prefill_or_score(m, p, host_seq_ids, host_lens, B, dev_tokens_packed, dev_ws, ws_bytes, dev_logits, nullptr, nullptr, stream);
+}
+
+extern "C" int spiral_score(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
+                            int B, const int32_t* dev_tokens_packed, const int32_t* dev_targets, void* dev_ws,
+                            size_t ws_bytes, float* dev_logp, void* stream) {
+    if (!dev_targets) return fail(SPIRAL_ERR_INVALID_ARG, "score: null targets");
+    int rc = check_common(m, p, dev_tokens_packed, dev_ws, dev_logp, "score");
+    if (rc) return rc;
+    if (!m->w_bf16) return fail(SPIRAL_ERR_SHAPE, "score: 16-bit weights only");
+    if (m->cfg.d_model % 128) return fail(SPIRAL_ERR_SHAPE, "score: d_model must be a multiple of 128");
+    return prefill_or_score(m, p, host_seq_ids, host_lens, B, dev_tokens_packed, dev_ws, ws_bytes, nullptr, dev_targets, dev_logp, stream);
+}
+
+extern "C" int spiral_policy_objective(const float* dev_logp_new, const float* dev_logp_old, const float* dev_advantage,
+                                       const int32_t* dev_mask, long long n, float clip_eps, double* dev_out2, void* stream) {
+    if (!dev_logp_new || !dev_logp_old || !dev_advantage || !dev_out2) return fail(SPIRAL_ERR_INVALID_ARG, "policy_objective: null pointer");
+    if (n < 0 || !(clip_eps >= 0.f) || !std::isfinite(clip_eps)) return fail(SPIRAL_ERR_INVALID_ARG, "policy_objective: bad n or clip parameter");
+    HIP_TRY(launch_score_objective(dev_logp_new, dev_logp_old, dev_advantage, dev_mask, n, clip_eps, dev_out2, (hipStream_t)stream));
+    return SPIRAL_OK;
 }
 
 extern "C" int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,

@@ -117,6 +117,18 @@ hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bo
 
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
                          const float* noise, int32_t* out, hipStream_t s);
+// scoring: per-row log-probability of a target token under the LM head's softmax
+struct ScoreArgs {
+    const void* A;            // act [M][K]: final-normed hidden states
+    const void* W;            // bf16 [V][K] LM head
+    const int32_t* targets;   // [M] target token of each row, < 0: none
+    float* part;              // [M][n_splits] (max, sum exp) pairs
+    float* tgt_logit;         // [M]
+    int32_t M, V, K, n_splits, tiles_per_split, m_tiles;
+};
+hipError_t launch_score(const ScoreArgs& a, float* out, hipStream_t s);
+hipError_t launch_score_objective(const float* logp_new, const float* logp_old, const float* adv, const int32_t* mask,
+                                  long long n, float eps, double* out, hipStream_t s);
 hipError_t launch_sample_truncated(const float* logits, int B, int V, float temperature, int top_k, float top_p,
                                    const uint64_t* host_keys, const float* noise, int32_t* out, float* tau_out,
                                    hipStream_t s);
