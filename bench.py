@@ -97,6 +97,72 @@ def algorithmic_bytes(g, lens_after_append, B):
     return weights + kv_read + kv_write + logits, kv_read // g.n_layers
 
 
+MFMA_PEAK_TFLOPS = 2500.0          # dense 16-bit MFMA peak of MI355X
+
+
+def prefill_report(g, prompts, seconds, score):
+    """Throughput of a packed causal forward over the prompts against the MFMA peak.  flops = 2 x matmul
+    parameters per token (+ the LM head on every row when scoring, on one row per sequence otherwise)
+    + 4 x hd x Hq per (token, visible token, layer) of attention."""
+    lens = np.array([len(p) for p in prompts], dtype=np.float64)
+    tokens = float(lens.sum())
+    flops = 2.0 * g.n_layers * g.params_per_layer() * tokens
+    flops += 4.0 * g.head_dim * g.n_q_heads * g.n_layers * float((lens * (lens + 1) / 2).sum())
+    flops += 2.0 * g.vocab * g.d_model * (tokens if score else len(prompts))
+    return {"tokens": int(tokens), "seconds": seconds, "tokens_per_s": tokens / seconds, "tflops": flops / seconds / 1e12,
+            "frac_of_mfma_peak": flops / seconds / 1e12 / MFMA_PEAK_TFLOPS}
+
+
+def next_rows(sess, sb, wl, prompts, ids, logits, group_tokens):
+    """Measurements of the rows built beyond the decode step: the learner-side scoring pass over the same
+    ragged histories (per-token log-probabilities, logits never written) and the truncated sampler in the
+    paper's evaluation setting (temperature 0.6, top-p 0.95) on the step's logits."""
+    import torch
+    g = wl.geometry
+    B = len(prompts)
+    sb.spiral_seq_reset(sess.pool, ids)
+    groups, i = [], 0
+    while i < B:
+        j, tok = i, 0
+        while j < B and (j == i or tok + len(prompts[j]) <= group_tokens):
+            tok += len(prompts[j]); j += 1
+        toks = torch.from_numpy(np.concatenate(prompts[i:j]).astype(np.int32)).to(sess.device)
+        tg = torch.from_numpy(np.concatenate([np.concatenate([p[1:], [-1]]) for p in prompts[i:j]]).astype(np.int32)).to(sess.device)
+        groups.append((np.arange(i, j, dtype=np.int32), [len(p) for p in prompts[i:j]], toks, tg,
+                       torch.empty(toks.numel(), dtype=torch.float32, device=sess.device)))
+        i = j
+    def score_all():
+        for gi, ln, toks, tg, out in groups:
+            sb.spiral_score(sess.model, sess.pool, gi, ln, toks, tg, sess.ws, out)
+        torch.cuda.synchronize()
+    score_all()
+    sb.spiral_seq_reset(sess.pool, ids)
+    t0 = time.time()
+    score_all()
+    score_s = time.time() - t0
+    rep = {"score": prefill_report(g, prompts, score_s, score=True)}
+    log(f"[bench] scoring pass over {rep['score']['tokens']} tokens: {score_s:.2f}s, {rep['score']['tflops']:.0f} TFLOP/s")
+
+    out_tok = torch.empty(B, dtype=torch.int32, device=sess.device)
+    steps = np.zeros(B, dtype=np.int32)
+    def timed(fn, n=20):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+    us_plain = timed(lambda: sb.spiral_sample(logits, B, g.vocab, 1.0, 1, ids, steps, None, out_tok))
+    us_trunc = timed(lambda: sb.spiral_sample_truncated(logits, B, g.vocab, 0.6, 0, 0.95, 1, ids, steps, None, out_tok, None))
+    nbytes = B * g.vocab * 4
+    rep["sample_truncated"] = {"setting": "T=0.6, top-p 0.95", "us": us_trunc, "us_untruncated": us_plain,
+                               "logits_bytes": nbytes, "GBps": nbytes / us_trunc / 1e3,
+                               "note": "6 passes over the row (max, 4 radix digits of probability mass, draw); ALU/LDS-atomic bound"}
+    log(f"[bench] sampler: untruncated {us_plain:.0f} us, T=0.6 top-p 0.95 {us_trunc:.0f} us")
+    return rep
+
+
 def cpu_baseline(wl, prompts, weights_dev, n_steps=3):
     """The oracle's KV-cached decoder (fp32 variant) on the host: one sequence of the batch (the
     shortest prompt), prompt consumed untimed, n_steps decode steps timed."""
@@ -138,6 +204,7 @@ def main():
     ap.add_argument("--prefill-group-tokens", type=int, default=8192)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the scoring-pass and truncated-sampler measurements")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference dispatch for "
                          "scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -168,6 +235,8 @@ def main():
     ids = np.arange(B, dtype=np.int32)
     seed = 1000 + wl.seed
 
+    prefill_all(sess, prompts, args.prefill_group_tokens)              # untimed first pass (code objects, caches)
+    sb.spiral_seq_reset(sess.pool, ids)
     t0 = time.time()
     logits = prefill_all(sess, prompts, args.prefill_group_tokens)
     prefill_s = time.time() - t0
@@ -231,6 +300,9 @@ def main():
         "prefill_s": prefill_s,
         "roofline": roofline,
     }
+    out["prefill"] = prefill_report(g, prompts, prefill_s, score=False)
+    if not args.no_extras and g.weight_dtype == 1 and g.d_model % 128 == 0:
+        out["next_rows"] = next_rows(sess, sb, wl, prompts, ids, logits, args.prefill_group_tokens)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, prompts, sess.weights)
     print(json.dumps(out), flush=True)
