@@ -39,18 +39,24 @@ constexpr int GROUP_M = 4;
 
 // SWIGLU: W rows of a tile are, per 32-row MFMA tile, 16 gate rows followed by the 16 up rows of the
 // same ffn columns (a workgroup covers 128 ffn columns); the epilogue applies SiLU(gate) * up in registers.
-template <bool SWIGLU>
+template <bool SWIGLU, int WMW>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
+    constexpr int BMT = 128 * WMW;                 // batch rows per workgroup
+    constexpr int WNW = 4 / WMW;                    // waves along the weight rows
+    constexpr int J = 256 / (32 * WNW);             // 32-row weight tiles per wave
+    constexpr int A_BYTES = BMT * ROW;              // activation tile; the weight tile follows it
+    constexpr int STAGE = A_BYTES + TILE_BYTES;
+    constexpr int AI = BMT / 32;                    // activation 16-byte segments per thread
     extern __shared__ uint4 lds_raw[];
     char* lds = (char*)lds_raw;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l32 = lane & 31, lh = lane >> 5;
-    const int wm = wave & 1, wn = wave >> 1;        // this wave's 128 x 128 quarter
+    const int wm = wave % WMW, wn = wave / WMW;     // this wave's 128 x (32 J) part of the tile
     const int K = g.K;
 
     // ---- tile of this workgroup
     const int n_cols = SWIGLU ? 128 : 256;          // output columns per workgroup
-    const int m_tiles = (g.M + BM - 1) / BM, n_tiles = (g.N + n_cols - 1) / n_cols;
+    const int m_tiles = (g.M + BMT - 1) / BMT, n_tiles = (g.N + n_cols - 1) / n_cols;
     const int total = m_tiles * n_tiles;
     const int per_xcd = (total + 7) / 8;
     const int t = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
@@ -59,18 +65,20 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     const int band_rows = min(GROUP_M, m_tiles - band * GROUP_M);
     const int tile_m = band * GROUP_M + (t % (GROUP_M * n_tiles)) % band_rows;
     const int tile_n = (t % (GROUP_M * n_tiles)) / band_rows;
-    const int m0 = tile_m * BM, n0 = tile_n * n_cols;
+    const int m0 = tile_m * BMT, n0 = tile_n * n_cols;
 
     // ---- global -> LDS assignment: 2048 16-byte segments per operand tile, 8 per thread (row = s / 8, column = s % 8)
-    const uint16_t* a_src[8];
+    const uint16_t* a_src[AI];
     const uint16_t* w_src[8];
     int dst[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int sgm = threadIdx.x + 256 * i;
         const int row = sgm >> 3, c8 = sgm & 7;
-        int m = m0 + row; if (m >= g.M) m = g.M - 1;
-        a_src[i] = (const uint16_t*)g.A + (size_t)m * K + c8 * 8;
+        if (i < AI) {
+            int m = m0 + row; if (m >= g.M) m = g.M - 1;
+            a_src[i] = (const uint16_t*)g.A + (size_t)m * K + c8 * 8;
+        }
         if (SWIGLU) {
             const int q = row >> 5, r = row & 31;
             int f = n0 + q * 16 + (r & 15); if (f >= g.N) f = g.N - 1;
@@ -87,53 +95,53 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     }
     // operand fragments: row (w? * 128 + j * 32 + l32), k = ks * 16 + lh * 8
     const int a_frag = (wm * 128 + l32) * ROW + lh * 16;
-    const int w_frag = TILE_BYTES + (wn * 128 + l32) * ROW + lh * 16;
+    const int w_frag = A_BYTES + (wn * 32 * J + l32) * ROW + lh * 16;
 
-    f32x16 acc[4][4];                               // [weight tile j][batch tile i]
+    f32x16 acc[J][4];                               // [weight tile j][batch tile i]
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < J; ++j)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
     const int NC = K / BK;
-    u32x4 ra[8], rw[8];
+    u32x4 ra[AI], rw[8];
     auto load = [&](int c) {
         const int cc = c < NC ? c : NC - 1;
         const size_t off = (size_t)cc * BK;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ra[i] = *(const u32x4*)(a_src[i] + off);
+        for (int i = 0; i < AI; ++i) ra[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
         for (int i = 0; i < 8; ++i) rw[i] = *(const u32x4*)(w_src[i] + off);
     };
     auto park = [&](int c) {
-        char* buf = lds + (c & 1) * STAGE_BYTES;
+        char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
+        for (int i = 0; i < AI; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + TILE_BYTES + dst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + dst[i]) = prep_w(rw[i]);
     };
     // One chunk: operand fragments of k step ks + 1 are read from LDS while the 16 MFMAs of step ks run.
     auto frags = [&](const char* buf, int ks, u32x4* af, u32x4* wf) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[i] = *(const u32x4*)(buf + a_frag + i * 32 * ROW + ks * 32);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wf[j] = *(const u32x4*)(buf + w_frag + j * 32 * ROW + ks * 32);
+        for (int j = 0; j < J; ++j) wf[j] = *(const u32x4*)(buf + w_frag + j * 32 * ROW + ks * 32);
     };
     auto park_a = [&](int c) {
-        char* buf = lds + (c & 1) * STAGE_BYTES;
+        char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
+        for (int i = 0; i < AI; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
     };
     auto park_w = [&](int c) {
-        char* buf = lds + (c & 1) * STAGE_BYTES;
+        char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + TILE_BYTES + dst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + dst[i]) = prep_w(rw[i]);
     };
     auto chunk = [&](int c) {
-        const char* buf = lds + (c & 1) * STAGE_BYTES;
-        u32x4 af[2][4], wf[2][4];
+        const char* buf = lds + (c & 1) * STAGE;
+        u32x4 af[2][4], wf[2][J];
         frags(buf, 0, af[0], wf[0]);
         load(c + 1);                                 // in flight during the arithmetic (past the end: a re-read)
 #pragma unroll
@@ -145,7 +153,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
             if (ks == 3) park_w(c + 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[j][i] = mma32t(wf[ks & 1][j], af[ks & 1][i], acc[j][i]);
             __builtin_amdgcn_sched_barrier(0);
@@ -167,10 +175,10 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
         for (int i = 0; i < 4; ++i) {
             const int m = m0 + wm * 128 + i * 32 + l32;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int b = 0; b < 4; ++b) {
-                    const int n = n0 + wn * 128 + j * 32 + 8 * b + 4 * lh;
+                    const int n = n0 + (wn * J + j) * 32 + 8 * b + 4 * lh;
                     if (m < g.M && n < g.N)
                         *(float4*)(out + (size_t)m * g.N + n) =
                             make_float4(acc[j][i][4 * b], acc[j][i][4 * b + 1], acc[j][i][4 * b + 2], acc[j][i][4 * b + 3]);
@@ -181,10 +189,10 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
         for (int i = 0; i < 4; ++i) {
             const int m = m0 + wm * 128 + i * 32 + l32;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) {
-                    const int f = n0 + (wn * 4 + j) * 16 + 8 * b + 4 * lh;
+                    const int f = n0 + (wn * J + j) * 16 + 8 * b + 4 * lh;
                     if (m < g.M && f < g.N) {
                         ushort4 o;
                         o.x = f32_to_act16(silu_f(acc[j][i][4 * b]) * acc[j][i][4 * b + 8]);
@@ -198,24 +206,25 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     }
 }
 
-hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, hipStream_t s) {
+template <bool SWIGLU, int WMW>
+static hipError_t launch_tile(const GemmArgs& a, hipStream_t s) {
+    const int cols = SWIGLU ? 128 : 256;
+    const int m_tiles = (a.M + 128 * WMW - 1) / (128 * WMW);
+    const int n_tiles = (a.N + cols - 1) / cols;
+    const int per_xcd = (m_tiles * n_tiles + 7) / 8;
+    const size_t lds_bytes = (size_t)2 * (128 * WMW * ROW + TILE_BYTES);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<SWIGLU, WMW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((gemm_tile_kernel<SWIGLU, WMW>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
+    return hipGetLastError();
+}
+
+// rows_per_tile: 256 (large M) or 128 (one tile of batch rows, weights streamed once through LDS)
+hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, int rows_per_tile, hipStream_t s) {
     if ((a.K % BK) || (a.N & 3) || a.splits != 1) return hipErrorInvalidValue;
     const bool swiglu = epilogue == EPI_SWIGLU;
-    const int m_tiles = (a.M + BM - 1) / BM;
-    const int n_tiles = (a.N + (swiglu ? 128 : 256) - 1) / (swiglu ? 128 : 256);
-    const int per_xcd = (m_tiles * n_tiles + 7) / 8;
-    const size_t lds_bytes = (size_t)2 * STAGE_BYTES;
-    hipError_t e;
-    if (swiglu) {
-        e = hipFuncSetAttribute((const void*)gemm_tile_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((gemm_tile_kernel<true>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
-    } else {
-        e = hipFuncSetAttribute((const void*)gemm_tile_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((gemm_tile_kernel<false>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
-    }
-    return hipGetLastError();
+    if (rows_per_tile == 128) return swiglu ? launch_tile<true, 1>(a, s) : launch_tile<false, 1>(a, s);
+    return swiglu ? launch_tile<true, 2>(a, s) : launch_tile<false, 2>(a, s);
 }
 
 }  // namespace spiral
