@@ -96,6 +96,16 @@ int  spiral_model_load(const spiral_model_config* cfg, const void* const* host_d
                        int n_weights, spiral_model** out);
 void spiral_model_free(spiral_model* m);
 
+/* Optional: copy the projection matrices and the LM head into the order the matrix-core operands are
+ * loaded in (1 KB blocks of 32 rows x 16 k; gate and up rows interleaved), so that every wave load
+ * reads whole cache lines.  dev_buffer: caller-owned device memory of at least
+ * spiral_model_repack_bytes(m) bytes (0: this geometry cannot be repacked), 256-byte aligned, which
+ * must stay valid as long as the model; the original weights must stay valid too (embedding rows,
+ * norms and biases are read from them).  The copies are enqueued on `stream`; calls that follow on the
+ * same stream use them.  Same results bit for bit.  Errors: NOT_LOADED, SHAPE, INVALID_ARG, HIP. */
+size_t spiral_model_repack_bytes(const spiral_model* m);
+int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* stream);
+
 /* Bytes of device workspace a prefill over at most max_rows packed prompt tokens, or a decode step
  * over at most max_rows sequences whose context is at most max_context tokens, needs.
  * Returns 0 on bad arguments. */

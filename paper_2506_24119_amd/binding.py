@@ -25,7 +25,7 @@ SPIRAL_MAX_BATCH = 1024
 SPIRAL_LAYER_SLOTS = 14
 
 EXPORTS = [
-    "spiral_last_error", "spiral_version", "spiral_model_load", "spiral_model_free",
+    "spiral_last_error", "spiral_version", "spiral_model_load", "spiral_model_free", "spiral_model_repack_bytes", "spiral_model_repack",
     "spiral_workspace_bytes", "spiral_kv_pool_bytes", "spiral_kv_pool_create", "spiral_kv_pool_free",
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
     "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
@@ -72,6 +72,10 @@ def load_library(path: Optional[str] = None):
     lib.spiral_version.argtypes = []
     lib.spiral_model_load.restype = C.c_int
     lib.spiral_model_load.argtypes = [C.POINTER(spiral_model_config), C.POINTER(C.c_void_p), C.c_int, C.POINTER(vp)]
+    lib.spiral_model_repack_bytes.restype = C.c_size_t
+    lib.spiral_model_repack_bytes.argtypes = [vp]
+    lib.spiral_model_repack.restype = C.c_int
+    lib.spiral_model_repack.argtypes = [vp, vp, C.c_size_t, vp]
     lib.spiral_model_free.restype = None
     lib.spiral_model_free.argtypes = [vp]
     lib.spiral_workspace_bytes.restype = C.c_size_t
@@ -323,13 +327,19 @@ class Session:
     It adds no computation of its own."""
 
     def __init__(self, g: _inputs.ModelGeometry, weights_dev: Dict[str, object], n_pages: int, max_seqs: int,
-                 max_blocks_per_seq: int, max_rows: int, max_context: int, page_order=None, device="cuda:0"):
+                 max_blocks_per_seq: int, max_rows: int, max_context: int, page_order=None, device="cuda:0",
+                 repack: bool = True):
         import torch
         self.torch = torch
         self.g = g
         self.device = torch.device(device)
         self.weights = weights_dev                       # keeps the tensors alive
         self.model = spiral_model_load(make_config(g), weight_pointer_table(g, weights_dev))
+        self.repacked = None
+        nbytes = load_library().spiral_model_repack_bytes(self.model) if repack else 0
+        if nbytes:
+            self.repacked = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            _check(load_library().spiral_model_repack(self.model, _ptr(self.repacked), C.c_size_t(nbytes), None))
         self.pool_mem = torch.empty(spiral_kv_pool_bytes(self.model, n_pages, max_seqs, max_blocks_per_seq),
                                     dtype=torch.uint8, device=self.device)
         self.pool = spiral_kv_pool_create(self.model, self.pool_mem, n_pages, max_seqs, max_blocks_per_seq, page_order)

@@ -43,7 +43,7 @@ struct Stage {
 
 // M32: batch tiles of 32 rows per workgroup; WN: waves along the weight rows (WM = 4 / WN along the
 // batch); SWIGLU: waves wn < WN/2 hold gate rows, the others the matching up rows.
-template <int M32, int WN, bool SWIGLU, int PD>
+template <int M32, int WN, bool SWIGLU, int PD, bool FRAG = false>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
     constexpr int WM = 4 / WN;
     constexpr int MW = M32 / WM;                    // batch tiles per wave
@@ -78,6 +78,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
         else if (n < g.rows[0] + g.rows[1]) { base = (const uint16_t*)g.w[1]; row = n - g.rows[0]; }
         else { base = (const uint16_t*)g.w[2]; row = n - g.rows[0] - g.rows[1]; }
         wrow = base + (size_t)row * K + lh * 8;
+        if (FRAG) {
+            const int t32 = min(tile_n * WN + wn, (g.N + 31) / 32 - 1);
+            wrow = (const uint16_t*)g.wf + frag_block(t32, 0, K) + lane * 8;
+        }
     }
 
     // ---- this thread's share of an activation chunk: 2*M32 segments of 16 B (row = s / 16, column = s % 16)
@@ -113,7 +117,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < 2 * M32; ++i) S.a[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) S.w[ks] = *(const u32x4*)(wrow + off + ks * 16);
+        for (int ks = 0; ks < 8; ++ks)
+            S.w[ks] = FRAG ? *(const u32x4*)(wrow + ((size_t)cc * 8 + ks) * 512) : *(const u32x4*)(wrow + off + ks * 16);
     };
     auto iter = [&](Stage<M32>& S, int c) {
         char* buf = lds + (c & 1) * BUF;
@@ -206,7 +211,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
 // exchange between waves.  NW waves per workgroup, each with all M32 batch tiles; NW is chosen on
 // the host so that the workgroups fill the 256 compute units in one round (9728 ffn columns are
 // 608 wave tiles: 203 workgroups of 3 use every unit at most 3 tiles deep, 152 of 4 leave 104 idle).
-template <int M32, int NW, int PD>
+template <int M32, int NW, int PD, bool FRAG = false>
 __global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
     constexpr int NT = 64 * NW;
     constexpr int ROWB = 272;
@@ -226,6 +231,8 @@ __global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
     const int f_first = (tile_n * NW + wave) * 16;  // first ffn column of this wave
     int f = f_first + (l32 & 15); if (f >= g.N) f = g.N - 1;
     const uint16_t* wrow = (const uint16_t*)(l32 < 16 ? g.w[0] : g.w[1]) + (size_t)f * K + lh * 8;
+    if (FRAG)       // the interleaved gate/up matrix: tile t holds ffn columns 16 t .. 16 t + 15
+        wrow = (const uint16_t*)g.wf + frag_block(min(tile_n * NW + wave, (g.N + 15) / 16 - 1), 0, K) + lane * 8;
 
     const uint16_t* a_src[AI];
     int a_dst[AI];
@@ -254,7 +261,8 @@ __global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < AI; ++i) S.a[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) S.w[ks] = *(const u32x4*)(wrow + off + ks * 16);
+        for (int ks = 0; ks < 8; ++ks)
+            S.w[ks] = FRAG ? *(const u32x4*)(wrow + ((size_t)cc * 8 + ks) * 512) : *(const u32x4*)(wrow + off + ks * 16);
     };
     auto iter = [&](St& S, int c) {
         char* buf = lds + (c & 1) * BUF;
@@ -314,7 +322,8 @@ static hipError_t launch_swiglu(const GemmArgs& a, hipStream_t s) {
     g.m_tiles = (a.M + 32 * M32 - 1) / (32 * M32);
     const int n_tiles = (a.N + 16 * NW - 1) / (16 * NW);
     const size_t lds_bytes = (size_t)2 * 32 * M32 * 272;
-    hipLaunchKernelGGL((swiglu_stream_kernel<M32, NW, PD>), dim3(n_tiles * g.m_tiles), dim3(64 * NW), lds_bytes, s, g);
+    if (a.wf) hipLaunchKernelGGL((swiglu_stream_kernel<M32, NW, PD, true>), dim3(n_tiles * g.m_tiles), dim3(64 * NW), lds_bytes, s, g);
+    else hipLaunchKernelGGL((swiglu_stream_kernel<M32, NW, PD, false>), dim3(n_tiles * g.m_tiles), dim3(64 * NW), lds_bytes, s, g);
     return hipGetLastError();
 }
 
@@ -339,8 +348,12 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     const int n_tiles = (a.N + cols - 1) / cols;
     size_t lds_bytes = (size_t)2 * 32 * M32 * 272;
     if (SWIGLU) lds_bytes = std::max(lds_bytes, (size_t)2 * M32 * 4 * 64 * sizeof(float4));
-    hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, SWIGLU, PD>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
-                       lds_bytes, s, g);
+    if (!SWIGLU && a.wf)
+        hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, false, PD, true>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
+                           lds_bytes, s, g);
+    else
+        hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, SWIGLU, PD, false>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
+                           lds_bytes, s, g);
     return hipGetLastError();
 }
 

@@ -39,7 +39,7 @@ constexpr int GROUP_M = 4;
 
 // SWIGLU: W rows of a tile are, per 32-row MFMA tile, 16 gate rows followed by the 16 up rows of the
 // same ffn columns (a workgroup covers 128 ffn columns); the epilogue applies SiLU(gate) * up in registers.
-template <bool SWIGLU, int WMW>
+template <bool SWIGLU, int WMW, bool FRAG>
 __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     constexpr int BMT = 128 * WMW;                 // batch rows per workgroup
     constexpr int WNW = 4 / WMW;                    // waves along the weight rows
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     // ---- global -> LDS assignment: 2048 16-byte segments per operand tile, 8 per thread (row = s / 8, column = s % 8)
     const uint16_t* a_src[AI];
     const uint16_t* w_src[8];
-    int dst[8];
+    int dst[8], wdst[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int sgm = threadIdx.x + 256 * i;
@@ -79,7 +79,16 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
             int m = m0 + row; if (m >= g.M) m = g.M - 1;
             a_src[i] = (const uint16_t*)g.A + (size_t)m * K + c8 * 8;
         }
-        if (SWIGLU) {
+        wdst[i] = row * ROW + c8 * 16;
+        if (FRAG) {
+            // fragment order (SwiGLU: the interleaved gate/up matrix): a wave reads whole 1 KB blocks.
+            // Unit u = threadIdx.x + 256 i of a chunk: lane = u % 64, (row tile rt, k step ks) = u / 64.
+            const int blk = (threadIdx.x >> 6) + 4 * i, rt = blk >> 2, ks = blk & 3;
+            const int t_all = SWIGLU ? (g.N + 15) / 16 : (g.N + 31) / 32;
+            const int t32 = min((SWIGLU ? n0 / 16 : n0 / 32) + rt, t_all - 1);
+            w_src[i] = (const uint16_t*)g.wf + frag_block(t32, ks, K) + lane * 8;
+            wdst[i] = (rt * 32 + l32) * ROW + ks * 32 + lh * 16;
+        } else if (SWIGLU) {
             const int q = row >> 5, r = row & 31;
             int f = n0 + q * 16 + (r & 15); if (f >= g.N) f = g.N - 1;
             w_src[i] = (const uint16_t*)(r < 16 ? g.w[0] : g.w[1]) + (size_t)f * K + c8 * 8;
@@ -113,14 +122,14 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < AI; ++i) ra[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) rw[i] = *(const u32x4*)(w_src[i] + off);
+        for (int i = 0; i < 8; ++i) rw[i] = *(const u32x4*)(w_src[i] + (FRAG ? (size_t)cc * (BK / 16) * 512 : off));
     };
     auto park = [&](int c) {
         char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
         for (int i = 0; i < AI; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + dst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = prep_w(rw[i]);
     };
     // One chunk: operand fragments of k step ks + 1 are read from LDS while the 16 MFMAs of step ks run.
     auto frags = [&](const char* buf, int ks, u32x4* af, u32x4* wf) {
@@ -137,7 +146,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     auto park_w = [&](int c) {
         char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + dst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = prep_w(rw[i]);
     };
     auto chunk = [&](int c) {
         const char* buf = lds + (c & 1) * STAGE;
@@ -206,16 +215,16 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     }
 }
 
-template <bool SWIGLU, int WMW>
+template <bool SWIGLU, int WMW, bool FRAG>
 static hipError_t launch_tile(const GemmArgs& a, hipStream_t s) {
     const int cols = SWIGLU ? 128 : 256;
     const int m_tiles = (a.M + 128 * WMW - 1) / (128 * WMW);
     const int n_tiles = (a.N + cols - 1) / cols;
     const int per_xcd = (m_tiles * n_tiles + 7) / 8;
     const size_t lds_bytes = (size_t)2 * (128 * WMW * ROW + TILE_BYTES);
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<SWIGLU, WMW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<SWIGLU, WMW, FRAG>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_tile_kernel<SWIGLU, WMW>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
+    hipLaunchKernelGGL((gemm_tile_kernel<SWIGLU, WMW, FRAG>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
     return hipGetLastError();
 }
 
@@ -223,8 +232,12 @@ static hipError_t launch_tile(const GemmArgs& a, hipStream_t s) {
 hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, int rows_per_tile, hipStream_t s) {
     if ((a.K % BK) || (a.N & 3) || a.splits != 1) return hipErrorInvalidValue;
     const bool swiglu = epilogue == EPI_SWIGLU;
-    if (rows_per_tile == 128) return swiglu ? launch_tile<true, 1>(a, s) : launch_tile<false, 1>(a, s);
-    return swiglu ? launch_tile<true, 2>(a, s) : launch_tile<false, 2>(a, s);
+    if (rows_per_tile == 128) {
+        if (a.wf) return swiglu ? launch_tile<true, 1, true>(a, s) : launch_tile<false, 1, true>(a, s);
+        return swiglu ? launch_tile<true, 1, false>(a, s) : launch_tile<false, 1, false>(a, s);
+    }
+    if (a.wf) return swiglu ? launch_tile<true, 2, true>(a, s) : launch_tile<false, 2, true>(a, s);
+    return swiglu ? launch_tile<true, 2, false>(a, s) : launch_tile<false, 2, false>(a, s);
 }
 
 }  // namespace spiral

@@ -1,6 +1,8 @@
 // Small memory-bound kernels of the decode path: embedding + RMSNorm, residual-add + RMSNorm,
 // the fused q/k/v post-processing (bias | per-head RMSNorm, RoPE, KV append), the Gumbel-max
 // sampler, and the by-value uploads that keep the library free of device allocations.
+#include <algorithm>
+
 #include "spiral_internal.h"
 
 namespace spiral {
@@ -330,6 +332,44 @@ hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s) {
     dim3 g(a.n_rows, (n_heads + 3) / 4), b(256);
     if (w_bf16) hipLaunchKernelGGL((qkv_post_kernel<true>), g, b, 0, s, a);
     else hipLaunchKernelGGL((qkv_post_kernel<false>), g, b, 0, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Weight repack: row-major [N][K] 16-bit rows -> fragment order (frag_block()).  Rows come from up to
+// three stacked blocks (q | k | v), or, interleaved, tile t takes rows 16 t .. 16 t + 15 of src0 (gate)
+// followed by the same rows of src1 (up).  Rows past the end are zero.  One thread per 16 bytes.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void repack_kernel(const uint16_t* s0, const uint16_t* s1, const uint16_t* s2, int r0, int r1,
+                                                     int r2, int K, int interleave16, uint4* dst, long long n_units) {
+    const int ksteps = K >> 4;
+    for (long long u = (long long)blockIdx.x * 256 + threadIdx.x; u < n_units; u += (long long)gridDim.x * 256) {
+        const int lane = (int)(u & 63);
+        const long long blk = u >> 6;
+        const int ks = (int)(blk % ksteps), t = (int)(blk / ksteps);
+        const int l32 = lane & 31, lh = lane >> 5;
+        const uint16_t* src = nullptr;
+        if (interleave16) {
+            const int row = t * 16 + (l32 & 15);
+            if (row < r0) src = (l32 < 16 ? s0 : s1) + (size_t)row * K;
+        } else {
+            int row = t * 32 + l32;
+            if (row < r0) src = s0 + (size_t)row * K;
+            else if (row < r0 + r1) src = s1 + (size_t)(row - r0) * K;
+            else if (row < r0 + r1 + r2) src = s2 + (size_t)(row - r0 - r1) * K;
+        }
+        dst[u] = src ? *(const uint4*)(src + ks * 16 + lh * 8) : make_uint4(0u, 0u, 0u, 0u);
+    }
+}
+
+hipError_t launch_repack(const void* src0, const void* src1, const void* src2, int rows0, int rows1, int rows2, int K,
+                         bool interleave16, void* dst, hipStream_t s) {
+    if (K & 15) return hipErrorInvalidValue;
+    const long long tiles = interleave16 ? (rows0 + 15) / 16 : (rows0 + rows1 + rows2 + 31) / 32;
+    const long long n_units = tiles * (K >> 4) * 64;
+    const int blocks = (int)std::min<long long>((n_units + 255) / 256, 65536);
+    hipLaunchKernelGGL(repack_kernel, dim3(blocks), dim3(256), 0, s, (const uint16_t*)src0, (const uint16_t*)src1,
+                       (const uint16_t*)src2, rows0, rows1, rows2, K, interleave16 ? 1 : 0, (uint4*)dst, n_units);
     return hipGetLastError();
 }
 

@@ -33,6 +33,7 @@ constexpr int PD = 2;
 
 }  // namespace
 
+template <bool FRAG>
 __global__ __launch_bounds__(256) void score_lmhead_kernel(ScoreArgs g) {
     extern __shared__ uint4 lds_raw[];
     char* lds = (char*)lds_raw;
@@ -74,7 +75,8 @@ __global__ __launch_bounds__(256) void score_lmhead_kernel(ScoreArgs g) {
     for (int nt = nt_begin; nt < nt_end; ++nt) {
         const int n_first = nt * 128 + wave * 32;
         int n = n_first + l32; if (n >= g.V) n = g.V - 1;
-        const uint16_t* wrow = (const uint16_t*)g.W + (size_t)n * K + lh * 8;
+        const uint16_t* wrow = FRAG ? (const uint16_t*)g.Wf + frag_block(min(nt * 4 + wave, (g.V + 31) / 32 - 1), 0, K) + lane * 8
+                                    : (const uint16_t*)g.W + (size_t)n * K + lh * 8;
 
         f32x16 acc[4];
 #pragma unroll
@@ -89,7 +91,8 @@ __global__ __launch_bounds__(256) void score_lmhead_kernel(ScoreArgs g) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) S.a[i] = *(const u32x4*)(a_src[i] + off);
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) S.w[ks] = *(const u32x4*)(wrow + off + ks * 16);
+            for (int ks = 0; ks < 8; ++ks)
+                S.w[ks] = FRAG ? *(const u32x4*)(wrow + ((size_t)cc * 8 + ks) * 512) : *(const u32x4*)(wrow + off + ks * 16);
         };
         auto iter = [&](St& S, int c) {
             char* buf = lds + (c & 1) * BUF;
@@ -216,7 +219,8 @@ hipError_t launch_score(const ScoreArgs& a, float* out, hipStream_t s) {
     if (a.M < 1 || a.V < 1 || (a.K & 127) || a.n_splits < 1 || a.tiles_per_split < 1) return hipErrorInvalidValue;
     ScoreArgs g = a;
     g.m_tiles = (a.M + 127) / 128;
-    hipLaunchKernelGGL(score_lmhead_kernel, dim3(g.m_tiles * g.n_splits), dim3(256), (size_t)2 * BUF, s, g);
+    if (g.Wf) hipLaunchKernelGGL(score_lmhead_kernel<true>, dim3(g.m_tiles * g.n_splits), dim3(256), (size_t)2 * BUF, s, g);
+    else hipLaunchKernelGGL(score_lmhead_kernel<false>, dim3(g.m_tiles * g.n_splits), dim3(256), (size_t)2 * BUF, s, g);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(score_merge_kernel, dim3((a.M + 255) / 256), dim3(256), 0, s, g, out);

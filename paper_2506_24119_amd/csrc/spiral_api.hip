@@ -56,6 +56,7 @@ struct Tune {
     int chunk_pages = 16;          // decode attention: pages per chunk (chunked kernel), least pages per workgroup (stream kernel)
     int attn_stream = 1;           // 1: balanced page stream over the whole batch; 0: one workgroup per chunk
     int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
+    int frag = 1;                  // 0: ignore spiral_model_repack (weights stay row-major; for A/B measurements)
 };
 constexpr int kMaxSplit = 16;
 constexpr int kScoreSplits = 64;       // vocabulary ranges of the scoring pass (partial log-sum-exp pairs per row)
@@ -74,6 +75,9 @@ struct spiral_model {
     RopeFreq freq;
     Tune tune;
     int n_cus = 256;
+    // fragment-ordered copies of the projection matrices (spiral_model_repack), null until then
+    std::vector<const void*> f_qkv, f_o, f_gu, f_down;
+    const void* f_lm = nullptr;
     const void* lw(int layer, int slot) const { return w[3 + layer * SPIRAL_LAYER_SLOTS + slot]; }
 };
 
@@ -116,6 +120,7 @@ static void parse_tune(Tune& t) {
                 else if (k == "chunk") { t.chunk_pages = a; }
                 else if (k == "stream") { t.attn_stream = a; }
                 else if (k == "wgs") { t.attn_wgs = a; }
+                else if (k == "frag") { t.frag = a; }
             }
         }
         i = j + 1;
@@ -195,6 +200,59 @@ static void drop_events(Profiler& p) {
 extern "C" void spiral_model_free(spiral_model* m) {
     if (m) drop_events(m->prof);
     delete m;
+}
+
+// ---------------------------------------------------------------------------------------------
+// weight repack into fragment order
+// ---------------------------------------------------------------------------------------------
+struct RepackPlan { size_t qkv, o, gu, down, lm, per_layer, total; bool ok; };
+
+static RepackPlan repack_plan(const spiral_model* m) {
+    const spiral_model_config& c = m->cfg;
+    const size_t d = c.d_model, qw = (size_t)c.n_q_heads * c.head_dim, kw = (size_t)c.n_kv_heads * c.head_dim, F = c.ffn_dim;
+    auto pad32 = [](size_t n) { return (n + 31) / 32 * 32; };
+    RepackPlan r;
+    r.ok = m->w_bf16 && d % 16 == 0 && qw % 16 == 0 && F % 16 == 0 && qw % 32 == 0 && kw % 32 == 0;
+    r.qkv = align256(pad32(qw + 2 * kw) * d * 2);
+    r.o = align256(pad32(d) * qw * 2);
+    r.gu = align256(2 * F * d * 2);
+    r.down = align256(pad32(d) * F * 2);
+    r.lm = align256(pad32(c.vocab) * d * 2);
+    r.per_layer = r.qkv + r.o + r.gu + r.down;
+    r.total = r.per_layer * c.n_layers + r.lm;
+    return r;
+}
+
+extern "C" size_t spiral_model_repack_bytes(const spiral_model* m) {
+    if (!m) return 0;
+    const RepackPlan r = repack_plan(m);
+    return r.ok ? r.total : 0;
+}
+
+extern "C" int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* stream) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "model_repack: null model");
+    const RepackPlan r = repack_plan(m);
+    if (!r.ok) return fail(SPIRAL_ERR_SHAPE, "model_repack: needs 16-bit weights and d_model, Hq*hd, Hkv*hd, ffn_dim multiples of 32 / 16");
+    if (!dev_buffer || ((uintptr_t)dev_buffer & 255) || bytes < r.total)
+        return fail(SPIRAL_ERR_INVALID_ARG, "model_repack: buffer null, not 256-byte aligned or smaller than %zu bytes", r.total);
+    if (!m->tune.frag) return SPIRAL_OK;
+    const spiral_model_config& c = m->cfg;
+    const int d = c.d_model, qw = c.n_q_heads * c.head_dim, kw = c.n_kv_heads * c.head_dim, F = c.ffn_dim;
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)dev_buffer;
+    std::vector<const void*> fq(c.n_layers), fo(c.n_layers), fg(c.n_layers), fd(c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        char* p = base + (size_t)l * r.per_layer;
+        fq[l] = p; fo[l] = p + r.qkv; fg[l] = p + r.qkv + r.o; fd[l] = p + r.qkv + r.o + r.gu;
+        HIP_TRY(launch_repack(m->lw(l, SPIRAL_W_Q), m->lw(l, SPIRAL_W_K), m->lw(l, SPIRAL_W_V), qw, kw, kw, d, false, (void*)fq[l], s));
+        HIP_TRY(launch_repack(m->lw(l, SPIRAL_W_O), nullptr, nullptr, d, 0, 0, qw, false, (void*)fo[l], s));
+        HIP_TRY(launch_repack(m->lw(l, SPIRAL_W_GATE), m->lw(l, SPIRAL_W_UP), nullptr, F, F, 0, d, true, (void*)fg[l], s));
+        HIP_TRY(launch_repack(m->lw(l, SPIRAL_W_DOWN), nullptr, nullptr, d, 0, 0, F, false, (void*)fd[l], s));
+    }
+    char* lm = base + (size_t)c.n_layers * r.per_layer;
+    HIP_TRY(launch_repack(m->w[2], nullptr, nullptr, c.vocab, 0, 0, d, false, lm, s));
+    m->f_qkv = fq; m->f_o = fo; m->f_gu = fg; m->f_down = fd; m->f_lm = lm;
+    return SPIRAL_OK;
 }
 
 extern "C" int spiral_profile_begin(spiral_model* m, int kernel_class, int max_launches) {
@@ -523,6 +581,7 @@ static int run_layers(StepCtx& c) {
         g.A = c.w.h; g.w[0] = m->lw(l, SPIRAL_W_Q); g.w[1] = m->lw(l, SPIRAL_W_K); g.w[2] = m->lw(l, SPIRAL_W_V);
         g.rows[0] = qw; g.rows[1] = kw; g.rows[2] = kw;
         g.M = c.rows; g.N = nqkv; g.K = d; g.out = c.w.qkv; g.splits = s_qkv;
+        g.wf = m->f_lm ? m->f_qkv[l] : nullptr;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, sh_qkv.bn, c.s); }));
 
         uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
@@ -553,6 +612,7 @@ static int run_layers(StepCtx& c) {
         GemmArgs go = {};
         go.A = c.w.o; go.w[0] = m->lw(l, SPIRAL_W_O); go.rows[0] = d;
         go.M = c.rows; go.N = d; go.K = qw; go.out = c.w.proj; go.splits = s_o;
+        go.wf = m->f_lm ? m->f_o[l] : nullptr;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_O, c.s, [&] { return launch_gemm(go, EPI_STORE_F32, m->w_bf16, sh_o.bn, c.s); }));
 
         NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps};
@@ -562,11 +622,13 @@ static int run_layers(StepCtx& c) {
         gu.A = c.w.h; gu.w[0] = m->lw(l, SPIRAL_W_GATE); gu.w[1] = m->lw(l, SPIRAL_W_UP);
         gu.rows[0] = cfg.ffn_dim; gu.rows[1] = cfg.ffn_dim;
         gu.M = c.rows; gu.N = cfg.ffn_dim; gu.K = d; gu.out = c.w.mlp; gu.splits = 1;
+        gu.wf = m->f_lm ? m->f_gu[l] : nullptr;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_GATE_UP, c.s, [&] { return launch_gemm(gu, EPI_SWIGLU, m->w_bf16, t.bn_gu, c.s); }));
 
         GemmArgs gd = {};
         gd.A = c.w.mlp; gd.w[0] = m->lw(l, SPIRAL_W_DOWN); gd.rows[0] = d;
         gd.M = c.rows; gd.N = d; gd.K = cfg.ffn_dim; gd.out = c.w.proj; gd.splits = s_down;
+        gd.wf = m->f_lm ? m->f_down[l] : nullptr;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_DOWN, c.s, [&] { return launch_gemm(gd, EPI_STORE_F32, m->w_bf16, sh_down.bn, c.s); }));
         pending = s_down;
     }
@@ -576,7 +638,7 @@ static int run_layers(StepCtx& c) {
         HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(na, act32, c.s); }));
         const int n_tiles = (cfg.vocab + 127) / 128;
         ScoreArgs sa = {};
-        sa.A = c.w.h; sa.W = m->w[2]; sa.targets = c.score_targets; sa.part = c.w.score_part; sa.tgt_logit = c.w.score_tgt;
+        sa.A = c.w.h; sa.W = m->w[2]; sa.Wf = m->f_lm; sa.targets = c.score_targets; sa.part = c.w.score_part; sa.tgt_logit = c.w.score_tgt;
         sa.M = c.rows; sa.V = cfg.vocab; sa.K = d;
         sa.tiles_per_split = (n_tiles + kScoreSplits - 1) / kScoreSplits;
         sa.n_splits = (n_tiles + sa.tiles_per_split - 1) / sa.tiles_per_split;
@@ -590,6 +652,7 @@ static int run_layers(StepCtx& c) {
     GemmArgs gl = {};
     gl.A = c.w.hf; gl.w[0] = m->w[2]; gl.rows[0] = cfg.vocab;
     gl.M = c.B; gl.N = cfg.vocab; gl.K = d; gl.out = c.logits; gl.splits = 1;
+    gl.wf = m->f_lm;
     HIP_TRY(timed(m, SPIRAL_K_GEMM_LM_HEAD, c.s, [&] { return launch_gemm(gl, EPI_STORE_F32, m->w_bf16, t.bn_lm, c.s); }));
     return SPIRAL_OK;
 }

@@ -36,6 +36,7 @@ enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_SWIGLU = 1 };
 struct GemmArgs {
     const void* A;        // activations [M][K] (act type)
     const void* w[3];     // weight row blocks, [rows][K]
+    const void* wf;       // or null: the same rows (SwiGLU: gate/up interleaved 16 + 16) in fragment order, see frag_block()
     int32_t rows[3];      // rows in each block
     int32_t M, N, K;      // N = total output columns (SwiGLU: ffn width)
     void* out;            // STORE_F32: fp32 [splits][M][N]; SWIGLU: act [M][N]
@@ -118,10 +119,20 @@ hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bo
 
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
                          const float* noise, int32_t* out, hipStream_t s);
+// Fragment order of a 16-bit weight matrix [N][K] (N padded to a multiple of 32, K % 16 == 0): 1 KB blocks
+// (32 rows x 16 k), block (t, ks) at element offset (t * (K / 16) + ks) * 512; inside a block lane
+// l = (k % 16 / 8) * 32 + row % 32 holds 8 consecutive k: exactly the operand registers of one
+// v_mfma_f32_32x32x16 step, so a wave's load instruction reads one contiguous block (8 cache lines
+// instead of 32 half-used ones).
+__host__ __device__ inline size_t frag_block(int t, int ks, int K) { return ((size_t)t * (K >> 4) + ks) * 512; }
+hipError_t launch_repack(const void* src0, const void* src1, const void* src2, int rows0, int rows1, int rows2, int K,
+                         bool interleave16, void* dst, hipStream_t s);
+
 // scoring: per-row log-probability of a target token under the LM head's softmax
 struct ScoreArgs {
     const void* A;            // act [M][K]: final-normed hidden states
     const void* W;            // bf16 [V][K] LM head
+    const void* Wf;           // or null: the LM head in fragment order
     const int32_t* targets;   // [M] target token of each row, < 0: none
     float* part;              // [M][n_splits] (max, sum exp) pairs
     float* tgt_logit;         // [M]
