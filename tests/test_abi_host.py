@@ -1,6 +1,7 @@
 """Host-only checks of the C ABI: the library loads, exports every symbol the
 header declares, validates arguments, and its RAE entry points match the
 oracle.  No GPU work is issued here."""
+import ctypes
 import os
 import re
 
@@ -110,3 +111,61 @@ def test_sample_argument_checks_need_no_gpu(lib):
         rc = lib.spiral_sample(None, 1, 8, 1.0, 0, None, None, None, None, None)
         sb._check(rc)
     assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+
+
+def test_new_entry_points_validate_arguments_without_a_gpu(lib):
+    """Truncated sampler, scoring pass, objective and repack reject bad arguments before any GPU call."""
+    def code(rc):
+        with pytest.raises(sb.SpiralError) as e:
+            sb._check(rc)
+        return e.value.code
+
+    fake = ctypes.c_void_p(0x10000)
+    # top_p outside (0, 1]
+    for bad_p in (0.0, -1.0, 1.5, float("nan")):
+        assert code(lib.spiral_sample_truncated(fake, 1, 8, 1.0, 0, bad_p, 0, None, None, None, fake, None, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    # greedy decoding has no threshold to report
+    assert code(lib.spiral_sample_truncated(fake, 1, 8, 0.0, 2, 0.9, 0, None, None, None, fake, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    # generated noise needs sequence ids and steps
+    assert code(lib.spiral_sample_truncated(fake, 1, 8, 1.0, 2, 0.9, 0, None, None, None, fake, None, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_sample_truncated(None, 1, 8, 1.0, 2, 0.9, 0, None, None, None, fake, None, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    # objective: null pointers, negative count, bad clip parameter
+    assert code(lib.spiral_policy_objective(None, fake, fake, None, 4, 0.2, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_policy_objective(fake, fake, fake, None, -1, 0.2, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_policy_objective(fake, fake, fake, None, 4, -0.1, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    # scoring and repack without a model
+    assert code(lib.spiral_score(None, None, None, None, 1, fake, fake, fake, 1024, fake, None)) == sb.SPIRAL_ERR_NOT_LOADED
+    assert code(lib.spiral_score(None, None, None, None, 1, fake, None, fake, 1024, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_model_repack(None, fake, 1 << 20, None)) == sb.SPIRAL_ERR_NOT_LOADED
+    assert lib.spiral_model_repack_bytes(None) == 0
+
+
+def test_repack_plan_and_buffer_checks(lib):
+    """Repack sizes follow the geometry (every matrix padded to 32 rows, gate/up interleaved into one); a
+    short or misaligned buffer is refused, and fp32 models cannot be repacked."""
+    g = si.ModelGeometry("rp", 2, 256, 8, 2, 128, 640, 1000, 1e6, qk_norm=True)
+    n = 3 + sb.SPIRAL_LAYER_SLOTS * g.n_layers
+    fake = [0x100000 + 0x1000 * i for i in range(n)]
+    cfg = sb.make_config(g)
+    m = sb.spiral_model_load(cfg, fake)
+    try:
+        a256 = lambda x: (x + 255) // 256 * 256
+        qw, kw, d, F = 8 * 128, 2 * 128, 256, 640
+        per_layer = a256((qw + 2 * kw) * d * 2) + a256(d * qw * 2) + a256(2 * F * d * 2) + a256(d * F * 2)
+        want = per_layer * 2 + a256(1024 * d * 2)                   # vocabulary 1000 padded to 1024 rows
+        assert lib.spiral_model_repack_bytes(m) == want
+        with pytest.raises(sb.SpiralError) as e:
+            sb._check(lib.spiral_model_repack(m, ctypes.c_void_p(0x200000), want - 1, None))
+        assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+        with pytest.raises(sb.SpiralError) as e:
+            sb._check(lib.spiral_model_repack(m, ctypes.c_void_p(0x200010), want, None))
+        assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+    finally:
+        sb.spiral_model_free(m)
+    g32 = si.ModelGeometry("rp32", 1, 128, 4, 2, 32, 512, 1024, 1e4, weight_dtype=0)
+    n = 3 + sb.SPIRAL_LAYER_SLOTS
+    m = sb.spiral_model_load(sb.make_config(g32), [0x100000 + 0x1000 * i for i in range(n)])
+    try:
+        assert lib.spiral_model_repack_bytes(m) == 0
+    finally:
+        sb.spiral_model_free(m)
