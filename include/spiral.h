@@ -223,8 +223,8 @@ int spiral_sample_truncated(const float* dev_logits, int B, int V, float tempera
  * ones run untimed).  Errors: INVALID_ARG (unknown class, max_launches < 1, begin while active,
  * end while inactive), HIP. */
 enum spiral_kernel_class {
-    SPIRAL_K_ATTN_DECODE = 0,   /* split-K paged decode attention (without the chunk merge) */
-    SPIRAL_K_ATTN_COMBINE,      /* merge of the per-chunk partial results */
+    SPIRAL_K_ATTN_DECODE = 0,   /* paged decode attention (without the merge of its partial results) */
+    SPIRAL_K_ATTN_COMBINE,      /* merge of the partial results */
     SPIRAL_K_ATTN_PREFILL,
     SPIRAL_K_GEMM_QKV, SPIRAL_K_GEMM_O, SPIRAL_K_GEMM_GATE_UP, SPIRAL_K_GEMM_DOWN, SPIRAL_K_GEMM_LM_HEAD,
     SPIRAL_K_NORM,              /* embedding / residual-add + RMSNorm kernels */

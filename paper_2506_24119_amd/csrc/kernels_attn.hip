@@ -13,8 +13,10 @@
 //
 // One workgroup = one tile x a range of pages; its four waves take pages round-robin, each with a
 // private online softmax (running max m, sum l, unnormalised O), merged through LDS at the end.
-// Decode splits the context into chunks of `chunk_pages` pages (one workgroup each, so that ragged
-// lengths spread over all CUs) and a second small kernel merges the chunks' (m, l, O).
+// Decode has two decompositions with the same inner loop: attn_stream_kernel (the default) cuts the
+// ordered stream of all (row, kv head, page) units of the batch into equal ranges, one per workgroup;
+// attn_kernel splits every sequence into chunks of `chunk_pages` pages, one workgroup each.  Either
+// way a second small kernel merges the partial (m, l, O) of a (row, head).
 // Softmax is evaluated in base 2: scores are scaled by log2(e)/sqrt(hd) and v_exp_f32 is 2^x.
 #include "spiral_internal.h"
 
