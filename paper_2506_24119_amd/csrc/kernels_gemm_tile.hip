@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < AI; ++i) *(u32x4*)(buf + dst[i]) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = FRAG ? rw[i] : prep_w(rw[i]);
     };
     // One chunk: operand fragments of k step ks + 1 are read from LDS while the 16 MFMAs of step ks run.
     auto frags = [&](const char* buf, int ks, u32x4* af, u32x4* wf) {
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     auto park_w = [&](int c) {
         char* buf = lds + (c & 1) * STAGE;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = prep_w(rw[i]);
+        for (int i = 0; i < 8; ++i) *(u32x4*)(buf + A_BYTES + wdst[i]) = FRAG ? rw[i] : prep_w(rw[i]);
     };
     auto chunk = [&](int c) {
         const char* buf = lds + (c & 1) * STAGE;

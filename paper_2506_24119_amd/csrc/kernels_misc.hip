@@ -4,6 +4,7 @@
 #include <algorithm>
 
 #include "spiral_internal.h"
+#include "mfma_ops.h"
 
 namespace spiral {
 
@@ -336,7 +337,7 @@ hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Weight repack: row-major [N][K] 16-bit rows -> fragment order (frag_block()).  Rows come from up to
+// Weight repack: row-major [N][K] bf16 rows -> fragment order (frag_block()), in the matrix cores' operand type.  Rows come from up to
 // three stacked blocks (q | k | v), or, interleaved, tile t takes rows 16 t .. 16 t + 15 of src0 (gate)
 // followed by the same rows of src1 (up).  Rows past the end are zero.  One thread per 16 bytes.
 // ---------------------------------------------------------------------------------------------
@@ -358,7 +359,11 @@ __global__ __launch_bounds__(256) void repack_kernel(const uint16_t* s0, const u
             else if (row < r0 + r1) src = s1 + (size_t)(row - r0) * K;
             else if (row < r0 + r1 + r2) src = s2 + (size_t)(row - r0 - r1) * K;
         }
-        dst[u] = src ? *(const uint4*)(src + ks * 16 + lh * 8) : make_uint4(0u, 0u, 0u, 0u);
+        uint4 v = src ? *(const uint4*)(src + ks * 16 + lh * 8) : make_uint4(0u, 0u, 0u, 0u);
+        // the copy holds the operand type of the matrix cores (bf16 widened to half exactly as the kernels
+        // do it in registers when they read row-major weights), so the GEMM kernels skip the conversion
+        const u32x4 c = prep_w(u32x4{v.x, v.y, v.z, v.w});
+        dst[u] = make_uint4(c.x, c.y, c.z, c.w);
     }
 }
 

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void score_lmhead_kernel(ScoreArgs g) {
                     for (int t = 0; t < 4; ++t)
                         af[(ks + 1) & 1][t] = *(const u32x4*)(buf + frag_off + t * 32 * ROWB + (ks + 1) * 32);
                 }
-                const u32x4 wp = prep_w(S.w[ks]);
+                const u32x4 wp = FRAG ? S.w[ks] : prep_w(S.w[ks]);      // fragment-ordered copies are already widened
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc[t] = mma32s(wp, af[ks & 1][t], acc[t]);
             }

@@ -196,6 +196,31 @@ def test_decode_attention_launch_shapes(sb, name, tune, monkeypatch):
     sess.close()
 
 
+def test_repacked_weights_give_bit_identical_logits(sb, monkeypatch):
+    """spiral_model_repack changes where the weight bytes sit and nothing else: prefill (small and large
+    row counts), decode and the scoring pass return the same bits with and without it."""
+    torch = _torch()
+    g = si.ModelGeometry("rp-check", 2, 256, 8, 2, 128, 640, 2000, 1e6, qk_norm=True)
+    w = si.make_weights(g, seed=27)
+    prompts = si.make_prompts(g.vocab, 6, 3, 200, seed=15)          # ~600 rows: the large-M kernels run too
+    forced = si.make_forced_tokens(g.vocab, 6, 5, seed=16)
+    outs = []
+    for tune in ("frag=0", "frag=1"):
+        monkeypatch.setenv("SPIRAL_TUNE", tune)
+        sess = make_session(sb, g, w, n_pages=96, max_seqs=8, max_blocks=16, max_rows=2048, max_context=256, page_seed=9)
+        assert (sess.repacked is not None)
+        logits, _ = run_teacher_forced(sb, sess, g, prompts, forced)
+        toks = torch.from_numpy(np.concatenate(prompts).astype(np.int32)).cuda()
+        tg = torch.from_numpy(np.concatenate([np.concatenate([p[1:], [-1]]) for p in prompts]).astype(np.int32)).cuda()
+        lp = torch.empty(toks.numel(), dtype=torch.float32, device="cuda")
+        sb.spiral_seq_reset(sess.pool, list(range(6)))
+        sb.spiral_score(sess.model, sess.pool, list(range(6)), [len(p) for p in prompts], toks, tg, sess.ws, lp)
+        outs.append((logits, lp.cpu().numpy()))
+        sess.close()
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+
+
 # ------------------------------------------------------------------------------------------------
 # invariants of the path itself
 # ------------------------------------------------------------------------------------------------
