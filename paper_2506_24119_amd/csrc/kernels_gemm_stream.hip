@@ -362,7 +362,13 @@ static hipError_t launch_shape(const GemmArgs& a, int bn, hipStream_t s) {
     // bn = weight rows per workgroup (128 or 64); narrower workgroups split the batch between waves
     if (a.M <= 32) return launch_one<1, 4, SWIGLU, 4>(a, s);
     if (a.M <= 64) return bn >= 128 ? launch_one<2, 4, SWIGLU, 3>(a, s) : launch_one<2, 2, SWIGLU, 3>(a, s);
-    return bn >= 128 ? launch_one<4, 4, SWIGLU, 2>(a, s) : launch_one<4, 2, SWIGLU, 3>(a, s);
+#ifndef STREAM_PD
+#define STREAM_PD 2
+#endif
+#ifndef SWIGLU_PD
+#define SWIGLU_PD 2
+#endif
+    return bn >= 128 ? launch_one<4, 4, SWIGLU, STREAM_PD>(a, s) : launch_one<4, 2, SWIGLU, 3>(a, s);
 }
 
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s) {
@@ -375,7 +381,7 @@ hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream
             const int nw = (bn == 96 || bn == 128 || bn == 160) ? bn / 32 : swiglu_waves(a.N, (a.M + rows_wg - 1) / rows_wg);
             if (a.M <= 32) return nw == 3 ? launch_swiglu<1, 3, 4>(a, s) : nw == 5 ? launch_swiglu<1, 5, 4>(a, s) : launch_swiglu<1, 4, 4>(a, s);
             if (a.M <= 64) return nw == 3 ? launch_swiglu<2, 3, 3>(a, s) : nw == 5 ? launch_swiglu<2, 5, 2>(a, s) : launch_swiglu<2, 4, 3>(a, s);
-            return nw == 3 ? launch_swiglu<4, 3, 2>(a, s) : nw == 5 ? launch_swiglu<4, 5, 2>(a, s) : launch_swiglu<4, 4, 2>(a, s);
+            return nw == 3 ? launch_swiglu<4, 3, SWIGLU_PD>(a, s) : nw == 5 ? launch_swiglu<4, 5, 2>(a, s) : launch_swiglu<4, 4, 2>(a, s);
         }
         return launch_shape<true>(a, bn, s);
     }
