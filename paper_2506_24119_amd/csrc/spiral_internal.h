@@ -109,7 +109,8 @@ struct QkvPostArgs {
 hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s);
 
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hipStream_t s);
-hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, int rows_per_tile, hipStream_t s);                 // K % 64 == 0, N % 4 == 0, no K split
+bool gemm_tile_usable(const GemmArgs& a);                                                  // fragment-ordered weights, K % 64 == 0, ...
+hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, hipStream_t s);
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s);   // K % 128 == 0, N % 16 == 0
 hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
