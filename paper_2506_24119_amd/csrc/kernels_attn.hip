@@ -11,8 +11,9 @@
 // head (padded to 16), so K and V are read once per group.  Prefill: the rows are 16 consecutive
 // positions of one query head, each with its own causal limit.
 //
-// One workgroup = one tile x a range of pages; its four waves take pages round-robin, each with a
-// private online softmax (running max m, sum l, unnormalised O), merged through LDS at the end.
+// Decode: one workgroup = one tile x a range of pages; its four waves take pages round-robin, each with
+// a private online softmax (running max m, sum l, unnormalised O), merged through LDS at the end.
+// Prefill (attn_prefill_kernel): one wave = one tile over all its pages, four heads per workgroup.
 // Decode has two decompositions with the same inner loop: attn_stream_kernel (the default) cuts the
 // ordered stream of all (row, kv head, page) units of the batch into equal ranges, one per workgroup;
 // attn_kernel splits every sequence into chunks of `chunk_pages` pages, one workgroup each.  Either
@@ -71,7 +72,7 @@ __device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, i
     for (int mp = 0; mp < HD / 32; ++mp) f.v[mp] = *(const u32x4*)((real ? vp : kp) + mp * step + off);
 }
 
-template <int HD, bool PREFILL, bool ACT32>
+template <int HD, bool ACT32>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     constexpr int KS = HD / 32, MT = HD / 16, OSTRIDE = HD + 4;
     __shared__ float s_o[4][16 * OSTRIDE];
@@ -85,23 +86,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 
     int seq, kvh, p_begin, p_end, limit, n_valid_rows;
     const uint16_t* qptr = nullptr;       // this lane's query row (row li of the tile) or null
-    int row0 = 0, head0 = 0;
-    if (PREFILL) {
-        const int b = blockIdx.z, h = blockIdx.y, qb = blockIdx.x;
-        const int r_first = a.cu_rows[b];
-        const int n_in_seq = a.cu_rows[b + 1] - r_first;
-        if (qb * 16 >= n_in_seq) return;
-        n_valid_rows = min(16, n_in_seq - qb * 16);
-        row0 = r_first + qb * 16;
-        head0 = h;
-        kvh = h / G;
-        seq = a.row_seq[row0];
-        const int pos0 = a.row_pos[row0];
-        limit = li < n_valid_rows ? pos0 + li : -1;
-        if (li < n_valid_rows) qptr = a.q + ((size_t)(row0 + li) * a.n_q_heads + h) * HD;
-        p_begin = 0;
-        p_end = (pos0 + n_valid_rows - 1) / kPageTokens + 1;
-    } else {
+    int row0 = 0;
+    {
         const int r = blockIdx.z, c = blockIdx.x;
         kvh = blockIdx.y;
         seq = a.row_seq[r];
@@ -112,7 +98,6 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         p_end = min(p_begin + a.chunk_pages, n_pages);
         n_valid_rows = G;
         row0 = r;
-        head0 = kvh * G;
         limit = pos;
         if (li < G) qptr = a.q + ((size_t)r * a.n_q_heads + kvh * G + li) * HD;
     }
@@ -219,13 +204,126 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             L += s_l[w][j] * sc;
             O += s_o[w][j * OSTRIDE + i] * sc;
         }
-        if (PREFILL) {
-            const size_t o_idx = ((size_t)(row0 + j) * a.n_q_heads + head0) * HD + i;
-            ActStore<ACT32>::put(a.out, o_idx, O / L);
-        } else {
-            float* dst = a.part + ((((size_t)row0 * a.n_kv_heads + kvh) * a.n_chunks + blockIdx.x) * G + j) * (HD + 2);
-            dst[i] = O;
-            if (i == 0) { dst[HD] = M; dst[HD + 1] = L; }
+        float* dst = a.part + ((((size_t)row0 * a.n_kv_heads + kvh) * a.n_chunks + blockIdx.x) * G + j) * (HD + 2);
+        dst[i] = O;
+        if (i == 0) { dst[HD] = M; dst[HD + 1] = L; }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Causal prefill attention.  A tile is 16 consecutive positions of one query head, each row with its own
+// causal limit; a workgroup holds four tiles, the same 16 positions of four adjacent heads, one per wave.
+// Every wave walks all pages of its tile alone (no merge between waves); with G = 4 the four waves share
+// a kv head and read the same pages at the same time, so K/V come from HBM/L2 once per workgroup.
+// ---------------------------------------------------------------------------------------------
+template <int HD, bool ACT32>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
+    constexpr int KS = HD / 32, MT = HD / 16;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int li = lane & 15, lg = lane >> 4;
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int b = blockIdx.z, qb = blockIdx.x;
+    const int h = blockIdx.y * 4 + wave;
+    const int r_first = a.cu_rows[b];
+    const int n_in_seq = a.cu_rows[b + 1] - r_first;
+    if (qb * 16 >= n_in_seq || h >= a.n_q_heads) return;          // no barriers below: waves are independent
+    const int n_valid_rows = min(16, n_in_seq - qb * 16);
+    const int row0 = r_first + qb * 16;
+    const int kvh = h / G;
+    const int seq = a.row_seq[row0];
+    const int pos0 = a.row_pos[row0];
+    const int limit = li < n_valid_rows ? pos0 + li : -1;
+    const int p_end = (pos0 + n_valid_rows - 1) / kPageTokens + 1;
+
+    u32x4 qf[KS];
+    {
+        const uint16_t* qptr = a.q + ((size_t)(row0 + (li < n_valid_rows ? li : 0)) * a.n_q_heads + h) * HD + lg * 8;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const u32x4 v = *(const u32x4*)(qptr + ks * 32);
+            qf[ks] = li < n_valid_rows ? v : u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.f;
+
+    const int32_t* bt = a.block_table + (size_t)seq * a.max_blocks;
+    const size_t page_elems = (size_t)a.n_kv_heads * (2 * kPageTokens * HD);
+    const size_t head_off = (size_t)kvh * (2 * kPageTokens * HD);
+
+    auto step = [&](const PageFrag<HD>& f, int pi) {
+        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], qf[ks], s);
+        const int t0 = pi * kPageTokens + lg * 4;
+        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
+        bool ok[4];
+        float mx = kNegBig;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            ok[r] = (t0 + r) <= limit;
+            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        float p[4];
+        float ps = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
+            ps += p[r];
+        }
+        l_run = l_run * alpha + ps;
+        const float m_prev = m_run;
+        m_run = m_new;
+        u32x2 pb;
+        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
+        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
+        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
+            }
+        }
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const u32x4 vv = f.v[mt >> 1];
+            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
+            acc[mt] = mma_pv(vt, pb, acc[mt]);
+        }
+    };
+
+    {
+        PageFrag<HD> cur, nxt;
+        int pi = 0;
+        load_page<HD>(cur, a.pages + (size_t)bt[0] * page_elems + head_off, lane, true);
+        while (true) {
+            const int pn = pi + 1;
+            const bool more = pn < p_end;
+            load_page<HD>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, lane, more);
+            step(cur, pi);
+            if (!more) break;
+            cur = nxt;
+            pi = pn;
+        }
+    }
+
+    // O^T[d][row]: lane (li, lg) holds d = mt * 16 + lg * 4 .. + 3 of row li; l is spread over the four lane groups
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (li < n_valid_rows) {
+        const float inv = 1.0f / l_run;
+        const size_t o_idx = ((size_t)(row0 + li) * a.n_q_heads + h) * HD + lg * 4;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 0, acc[mt].x * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 1, acc[mt].y * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 2, acc[mt].z * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 3, acc[mt].w * inv);
         }
     }
 }
@@ -531,7 +629,7 @@ hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hip
 
 template <int HD, bool ACT32>
 static hipError_t decode_impl(const AttnArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((attn_kernel<HD, false, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((attn_kernel<HD, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -564,7 +662,7 @@ hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_
 template <int HD, bool ACT32>
 static hipError_t prefill_impl(const AttnArgs& a, int B, int max_new, hipStream_t s) {
     const int qblocks = (max_new + 15) / 16;
-    hipLaunchKernelGGL((attn_kernel<HD, true, ACT32>), dim3(qblocks, a.n_q_heads, B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL((attn_prefill_kernel<HD, ACT32>), dim3(qblocks, (a.n_q_heads + 3) / 4, B), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
