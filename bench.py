@@ -163,7 +163,7 @@ def next_rows(sess, sb, wl, prompts, ids, logits, group_tokens):
     return rep
 
 
-def cpu_baseline(wl, prompts, weights_dev, n_steps=3):
+def cpu_baseline(wl, prompts, weights_dev, n_steps=48):
     """The oracle's KV-cached decoder (fp32 variant) on the host: one sequence of the batch (the
     shortest prompt), prompt consumed untimed, n_steps decode steps timed."""
     from oracle import decoder as od
