@@ -10,8 +10,8 @@
 // fragments from LDS (one step ahead of their use) for 16 v_mfma_f32_32x32x16 (256 accumulator
 // registers), i.e. 128 flop per byte fetched from L2 against 64 for a 128 x 128 tile; the issue order of
 // a step is pinned (8 LDS reads, then 4 x (4 MFMAs, 1 LDS write)) so that LDS traffic runs under the
-// MFMAs.  An isolated inner loop of this shape reaches 73 % of the MFMA peak (LDS reads 61 B/clk/CU,
-// one MFMA per 39 cycles); the kernel 0.67-0.98 PFLOP/s at 8192 rows, where 320 tiles of the two
+// MFMAs.  An isolated inner loop of this shape reaches 73 % of the MFMA peak (one MFMA per 39 cycles
+// back to back, 45 B/clk of LDS operand reads beside them); the kernel 0.67-0.98 PFLOP/s at 8192 rows, where 320 tiles of the two
 // narrow projections fill 256 CUs 1.25 times (the vendor GEMM: 1.0-1.4 PFLOP/s on these shapes).
 // Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the tile order is arranged so
 // that each XCD (own L2) gets a contiguous run of tiles, ordered in bands of 4 row tiles.
