@@ -335,19 +335,22 @@ def test_games_of_different_lengths_share_the_batch(sb):
     sess.close()
 
 
-def test_large_decode_batch_spans_row_tiles_and_upload_chunks(sb):
-    """300 sequences in one decode call: more than one 128-row GEMM tile, more than one by-value upload
-    of ids / page counts, and an attention stream whose workgroup ranges each hold many short sequences."""
+@pytest.mark.parametrize("B", [300, 1024])
+def test_large_decode_batch_spans_row_tiles_and_upload_chunks(sb, B):
+    """300 and 1024 (the most a call takes) sequences in one decode call: more than one 128-row GEMM tile (the
+    large-M kernels at 1024), several by-value uploads of ids / page counts, and an attention stream whose
+    workgroup ranges each hold many short sequences."""
     g = SMALL["g2-qknorm"]
     w = si.make_weights(g, seed=28)
-    B, steps = 300, 3
+    steps = 3
     prompts = si.make_prompts(g.vocab, B, 1, 40, seed=17)
     forced = si.make_forced_tokens(g.vocab, B, steps, seed=18)
     n_pages = sum((len(p) + steps + 16) // 16 for p in prompts) + 4
-    sess = make_session(sb, g, w, n_pages=n_pages, max_seqs=B, max_blocks=4, max_rows=8192, max_context=64, page_seed=10)
+    sess = make_session(sb, g, w, n_pages=n_pages, max_seqs=B, max_blocks=4, max_rows=sum(len(p) for p in prompts),
+                        max_context=64, page_seed=10)
     got_logits, got_tok = run_teacher_forced(sb, sess, g, prompts, forced)
     worst = 0.0
-    for b in list(range(0, B, 7)) + [127, 128, 129, 255, 256, 299]:
+    for b in list(range(0, B, 29)) + [127, 128, 129, 255, 256, B - 1]:
         want = oracle_teacher_forced(g, w, prompts[b], forced[:, b])
         worst = max(worst, assert_logits_close(got_logits[:, b], want, f"large batch seq {b}"))
     print(f"B = {B}: max|dlogit|/std = {worst:.3e}")
