@@ -20,7 +20,14 @@
  *    the default stream).  Host arrays are consumed before the call returns.
  *  - Opaque host objects (model, pool, RAE state) are created and freed by the
  *    library.  Calls on the same object must not overlap.
- *  - A failed call leaves sequence lengths and page tables unchanged.
+ *  - A failed call leaves sequence lengths and page tables unchanged: the sequences' lengths, their page lists
+ *    and the free list are host-side state that is advanced only after every launch of the call was accepted
+ *    (pages taken earlier in the call are returned).  After SPIRAL_ERR_HIP some kernels of the call may already
+ *    be enqueued; they write only beyond the sequences' recorded lengths and into the workspace.
+ *  - Precision: 16-bit weights are bf16 as given; activations, q, the cached K/V and the softmax weights are IEEE
+ *    half, all sums are fp32.  A value outside half's range (|x| > 65504) is stored as +-65504 and a NaN stays a
+ *    NaN; every such store increments a counter in the KV pool (spiral_kv_pool_status_offset) so that a caller
+ *    running a checkpoint with large activations can detect it.
  */
 #ifndef SPIRAL_H
 #define SPIRAL_H
@@ -106,6 +113,17 @@ void spiral_model_free(spiral_model* m);
 size_t spiral_model_repack_bytes(const spiral_model* m);
 int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* stream);
 
+/* Measurement / test hook: overrides the launch decomposition the library would choose from the geometry.
+ * spec is a comma-separated list of key=value items (unknown keys are ignored): "qkv=R:S", "o=R:S", "down=R:S"
+ * (weight rows per workgroup : K splits of that projection), "gu=R", "lm=R", "chunk=P" (least pages per
+ * attention workgroup), "stream=0|1" (decode attention as one balanced page stream, or one workgroup per chunk
+ * of P pages), "wgs=N" (workgroups of the stream kernel), "frag=0|1" (use the repacked weights), "slice=0|1"
+ * (narrow projections with the activation slice resident in LDS), "fail_after=N" (error-path tests: the N-th
+ * kernel launch of the layer stack from now on is not made and reports a launch failure).  Results stay within
+ * the parity tolerance for every setting; the defaults are the measured best.  "frag" must be set before
+ * spiral_model_repack, the others at any time between calls.  Errors: NOT_LOADED, INVALID_ARG. */
+int spiral_model_tune(spiral_model* m, const char* spec);
+
 /* Bytes of device workspace a prefill over at most max_rows packed prompt tokens, or a decode step
  * over at most max_rows sequences whose context is at most max_context tokens, needs.
  * Returns 0 on bad arguments. */
@@ -114,9 +132,10 @@ size_t spiral_workspace_bytes(const spiral_model* m, int max_rows, int max_conte
 /* ---- paged KV cache ---------------------------------------------------------------------------
  * One pool holds the K and V of every layer for up to max_seqs sequences in n_pages pages of 16
  * tokens; a sequence owns at most max_blocks_per_seq pages.  Layout inside dev_mem (all managed by
- * the library): block table int32 [max_seqs, max_blocks_per_seq], lengths int32 [max_seqs], then the
+ * the library): block table int32 [max_seqs, max_blocks_per_seq], a 256-byte status block, then the
  * pages, 16-bit (IEEE half): [layer][page][kv_head]{ K (16 tokens x head_dim), V (head_dim x 16 tokens) },
- * each stored in the element order of the matrix-core operands (an internal layout).
+ * each stored in the element order of the matrix-core operands (an internal layout).  Sequence lengths are
+ * host-side state of the pool object.
  * spiral_kv_pool_bytes gives the size dev_mem must have (0 on bad arguments); dev_mem must be
  * 256-byte aligned.  host_page_order (n_pages distinct ids in [0,n_pages), or NULL for ascending)
  * is the order in which free pages are handed out.  Creation enqueues a zero fill of the pool on
@@ -126,7 +145,12 @@ int    spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_t bytes,
                              int max_seqs, int max_blocks_per_seq, const int32_t* host_page_order,
                              void* stream, spiral_kv_pool** out);
 void   spiral_kv_pool_free(spiral_kv_pool* p);
-/* Empties the listed sequences and returns their pages to the free list (in reverse order of use). */
+/* Byte offset inside dev_mem of the pool's status block: int32 [0] counts the activation values that did not
+ * fit the 16-bit format since the pool was created (see "Precision" above; 0 in a healthy run).  The caller
+ * reads it with a copy of its own, after synchronising the stream.  Negative error code on a null pool. */
+long long spiral_kv_pool_status_offset(const spiral_kv_pool* p);
+/* Empties the listed sequences and returns their pages to the free list (in reverse order of use).  Host-side
+ * bookkeeping only: nothing is enqueued (`stream` is accepted for symmetry and ignored). */
 int    spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, int n, void* stream);
 /* Shortens the listed sequences to host_new_lens[i] tokens (0 <= new length <= current length) and
  * returns the pages that are no longer needed; the cached K/V of the kept prefix stay valid.  Used
@@ -159,6 +183,17 @@ int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_i
 int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
                        const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes,
                        float* dev_logits, void* stream);
+
+/* One decode step fused with the actor's sampler: as spiral_decode_step followed by spiral_sample with generated
+ * noise (seed, seq_id = host_seq_ids[i], step = host_steps[i]), bit for bit the same tokens, but the [B, vocab]
+ * logits are never written: the LM head keeps the best score of every 128-column tile per row and a small
+ * kernel picks the winner.  temperature == 0 is greedy decoding (host_steps may be NULL).  dev_out_tokens:
+ * int32 [B]; it may be the same buffer as dev_in_tokens (free-running generation feeds the samples back).
+ * Needs 16-bit weights repacked by spiral_model_repack, d_model % 128 == 0 and vocab % 16 == 0 (SHAPE error
+ * otherwise; use the two separate calls then).  Workspace and other errors as spiral_decode_step. */
+int spiral_decode_sample_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                              const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float temperature,
+                              uint64_t seed, const int32_t* host_steps, int32_t* dev_out_tokens, void* stream);
 
 /* ---- scoring pass (learner side) ---------------------------------------------------------------
  * The policy update of the paper (Alg. 1, last step; policy-gradient equation of Sec. 3) weights
@@ -229,6 +264,7 @@ enum spiral_kernel_class {
     SPIRAL_K_GEMM_QKV, SPIRAL_K_GEMM_O, SPIRAL_K_GEMM_GATE_UP, SPIRAL_K_GEMM_DOWN, SPIRAL_K_GEMM_LM_HEAD,
     SPIRAL_K_NORM,              /* embedding / residual-add + RMSNorm kernels */
     SPIRAL_K_QKV_POST,          /* bias | q/k norm + RoPE + KV append */
+    SPIRAL_K_SAMPLE,            /* winner among the per-tile results of the fused LM head + sampler */
     SPIRAL_K_CLASSES
 };
 int spiral_profile_begin(spiral_model* m, int kernel_class, int max_launches);

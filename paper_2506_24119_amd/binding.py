@@ -29,7 +29,7 @@ EXPORTS = [
     "spiral_workspace_bytes", "spiral_kv_pool_bytes", "spiral_kv_pool_create", "spiral_kv_pool_free",
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
     "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
-    "spiral_rae_free",
+    "spiral_rae_free", "spiral_model_tune", "spiral_kv_pool_status_offset", "spiral_decode_sample_step",
 ]
 
 
@@ -102,6 +102,12 @@ def load_library(path: Optional[str] = None):
     lib.spiral_prefill.argtypes = [vp, vp, i32p, i32p, C.c_int, vp, vp, C.c_size_t, f32p, vp]
     lib.spiral_decode_step.restype = C.c_int
     lib.spiral_decode_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, f32p, vp]
+    lib.spiral_decode_sample_step.restype = C.c_int
+    lib.spiral_decode_sample_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, C.c_float, C.c_uint64, i32p, vp, vp]
+    lib.spiral_model_tune.restype = C.c_int
+    lib.spiral_model_tune.argtypes = [vp, C.c_char_p]
+    lib.spiral_kv_pool_status_offset.restype = C.c_longlong
+    lib.spiral_kv_pool_status_offset.argtypes = [vp]
     lib.spiral_sample.restype = C.c_int
     lib.spiral_sample.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp, vp]
     lib.spiral_score.restype = C.c_int
@@ -219,7 +225,7 @@ def spiral_seq_truncate(pool: int, seq_ids, new_lens, stream=None):
 
 
 KERNEL_CLASSES = ["attn_decode", "attn_combine", "attn_prefill", "gemm_qkv", "gemm_o", "gemm_gate_up",
-                  "gemm_down", "gemm_lm_head", "norm", "qkv_post"]
+                  "gemm_down", "gemm_lm_head", "norm", "qkv_post", "sample"]
 
 
 def spiral_profile_begin(model: int, kernel_class: int, max_launches: int):
@@ -258,6 +264,27 @@ def spiral_decode_step(model: int, pool: int, seq_ids, dev_in_tokens, dev_ws, de
                                              _ptr(dev_ws),
                                              0 if dev_ws is None else dev_ws.numel() * dev_ws.element_size(),
                                              _ptr(dev_logits), _stream_handle(stream)))
+
+
+def spiral_decode_sample_step(model: int, pool: int, seq_ids, dev_in_tokens, dev_ws, temperature: float, seed: int, steps,
+                              dev_out_tokens, stream=None):
+    ids = seq_ids if isinstance(seq_ids, np.ndarray) and seq_ids.dtype == np.int32 else _i32(seq_ids)
+    st = None if steps is None else (steps if isinstance(steps, np.ndarray) and steps.dtype == np.int32 else _i32(steps))
+    _check(load_library().spiral_decode_sample_step(model, pool, _ip(ids), int(ids.shape[0]), _ptr(dev_in_tokens), _ptr(dev_ws),
+                                                    0 if dev_ws is None else dev_ws.numel() * dev_ws.element_size(),
+                                                    C.c_float(temperature), C.c_uint64(seed), _ip(st), _ptr(dev_out_tokens),
+                                                    _stream_handle(stream)))
+
+
+def spiral_model_tune(model: int, spec: str):
+    _check(load_library().spiral_model_tune(model, spec.encode()))
+
+
+def spiral_kv_pool_status_offset(pool: int) -> int:
+    off = load_library().spiral_kv_pool_status_offset(pool)
+    if off < 0:
+        _check(int(off))
+    return int(off)
 
 
 def spiral_sample(dev_logits, B: int, V: int, temperature: float, seed: int, seq_ids, steps, dev_noise,
@@ -328,13 +355,15 @@ class Session:
 
     def __init__(self, g: _inputs.ModelGeometry, weights_dev: Dict[str, object], n_pages: int, max_seqs: int,
                  max_blocks_per_seq: int, max_rows: int, max_context: int, page_order=None, device="cuda:0",
-                 repack: bool = True):
+                 repack: bool = True, tune: Optional[str] = None):
         import torch
         self.torch = torch
         self.g = g
         self.device = torch.device(device)
         self.weights = weights_dev                       # keeps the tensors alive
         self.model = spiral_model_load(make_config(g), weight_pointer_table(g, weights_dev))
+        if tune:
+            spiral_model_tune(self.model, tune)
         self.repacked = None
         nbytes = load_library().spiral_model_repack_bytes(self.model) if repack else 0
         if nbytes:
@@ -360,6 +389,15 @@ class Session:
     def decode_step(self, seq_ids, dev_in_tokens, logits):
         spiral_decode_step(self.model, self.pool, seq_ids, dev_in_tokens, self.ws, logits)
         return logits
+
+    def decode_sample_step(self, seq_ids, dev_in_tokens, temperature: float, seed: int, steps, out_tokens):
+        spiral_decode_sample_step(self.model, self.pool, seq_ids, dev_in_tokens, self.ws, temperature, seed, steps, out_tokens)
+        return out_tokens
+
+    def saturation_count(self) -> int:
+        """Activation values that did not fit the 16-bit format since the pool was created (synchronises)."""
+        off = spiral_kv_pool_status_offset(self.pool)
+        return int(self.pool_mem[off:off + 4].view(self.torch.int32).cpu().item())
 
     def sample(self, logits, temperature: float, seed: int, seq_ids, steps, out_tokens, noise=None):
         spiral_sample(logits, logits.shape[0], logits.shape[1], temperature, seed, seq_ids, steps, noise, out_tokens)

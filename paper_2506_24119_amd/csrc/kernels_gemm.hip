@@ -152,6 +152,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
         }
     } else {
         constexpr int H = NT / 2;
+        bool bad = false;
 #pragma unroll
         for (int ft = 0; ft < H; ++ft) {
 #pragma unroll
@@ -176,15 +177,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
                 const int f = tile_n * (16 * H) + ft * 16 + lg * 4;
                 if (m < g.M && f < g.N) {
                     ushort4 o;
-                    o.x = f32_to_act16(silu_f(gs.x) * us.x);
-                    o.y = f32_to_act16(silu_f(gs.y) * us.y);
-                    o.z = f32_to_act16(silu_f(gs.z) * us.z);
-                    o.w = f32_to_act16(silu_f(gs.w) * us.w);
+                    o.x = f32_to_act16_noting(silu_f(gs.x) * us.x, bad);
+                    o.y = f32_to_act16_noting(silu_f(gs.y) * us.y, bad);
+                    o.z = f32_to_act16_noting(silu_f(gs.z) * us.z, bad);
+                    o.w = f32_to_act16_noting(silu_f(gs.w) * us.w, bad);
                     *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
                 }
             }
             __syncthreads();
         }
+        report_saturation(g.sat_count, bad);
     }
 }
 

@@ -54,7 +54,7 @@ struct Stage {
 
 // M32: batch tiles of 32 rows per workgroup; WN: waves along the weight rows (WM = 4 / WN along the
 // batch); SWIGLU: waves wn < WN/2 hold gate rows, the others the matching up rows.
-template <int M32, int WN, bool SWIGLU, int PD, bool FRAG = false>
+template <int M32, int WN, bool SWIGLU, int PD, bool FRAG = false, bool SAMPLE = false>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
     constexpr int WM = 4 / WN;
     constexpr int MW = M32 / WM;                    // batch tiles per wave
@@ -167,7 +167,46 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
 
     // ---- epilogue.  Accumulator layout of the 32x32 tile: lane holds batch row l32 and, in registers
     //      4b .. 4b+3, the weight rows 8b + 4*lh .. +3 (b = 0..3): four consecutive output columns each.
-    if (!SWIGLU) {
+    if (!SWIGLU && SAMPLE) {
+        // LM head without logits: score = logit / T + noise (the sampler's own expression), the best (score, index)
+        // of the workgroup's columns per batch row goes to s_part[row][tile_n]; a second kernel picks among tiles.
+        constexpr int R = 32 * M32;
+        __syncthreads();                             // every wave is done with the activation buffers
+        float* s_val = (float*)lds;                  // [WN][R]
+        int* s_idx = (int*)(lds + WN * R * 4);
+        const float T = g.s_temperature;
+#pragma unroll
+        for (int t = 0; t < MW; ++t) {
+            const int row = (wm * MW + t) * 32 + l32;
+            const int m = m0 + row;
+            const uint64_t key = (T > 0.f && m < g.M) ? g.s_keys[m] : 0ull;
+            float bv = -INFINITY;
+            int bi = 0x7FFFFFFF;
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int n = n_first + 8 * b + 4 * lh + i;
+                    float sc = acc[t][4 * b + i];
+                    if (T > 0.f) sc = sc / T + gumbel_noise(key, n);
+                    if (n < g.N && better(sc, n, bv, bi)) { bv = sc; bi = n; }
+                }
+            const float ov = __shfl_xor(bv, 32, 64);
+            const int oi = __shfl_xor(bi, 32, 64);
+            if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+            if (lh == 0) { s_val[wn * R + row] = bv; s_idx[wn * R + row] = bi; }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < R) {
+            const int row = threadIdx.x, m = m0 + row;
+            float bv = s_val[row];
+            int bi = s_idx[row];
+#pragma unroll
+            for (int w = 1; w < WN; ++w)
+                if (better(s_val[w * R + row], s_idx[w * R + row], bv, bi)) { bv = s_val[w * R + row]; bi = s_idx[w * R + row]; }
+            if (m < g.M) g.s_part[(size_t)m * g.s_tiles + tile_n] = make_float2(bv, __int_as_float(bi));
+        }
+    } else if (!SWIGLU) {
         // Stores go through LDS so that every store instruction writes whole 128-byte lines (8 lanes x 16 B per
         // row, 8 rows): written straight from the accumulator layout a wave store touches 32 rows x 32 B, and the
         // partial-line traffic costs a quarter of the kernel (LM head 188 -> 143 us without its stores).
@@ -209,6 +248,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
         }
         __syncthreads();
         if (wn >= H) return;
+        bool bad = false;
 #pragma unroll
         for (int t = 0; t < MW; ++t) {
             const int m = m0 + (wm * MW + t) * 32 + l32;
@@ -218,14 +258,15 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(GemmArgs g) {
                 const float4 u = x[((pair * MW + t) * 4 + b) * 64 + lane];
                 if (m < g.M && f < g.N) {
                     ushort4 o;
-                    o.x = f32_to_act16(silu_f(acc[t][4 * b]) * u.x);
-                    o.y = f32_to_act16(silu_f(acc[t][4 * b + 1]) * u.y);
-                    o.z = f32_to_act16(silu_f(acc[t][4 * b + 2]) * u.z);
-                    o.w = f32_to_act16(silu_f(acc[t][4 * b + 3]) * u.w);
+                    o.x = f32_to_act16_noting(silu_f(acc[t][4 * b]) * u.x, bad);
+                    o.y = f32_to_act16_noting(silu_f(acc[t][4 * b + 1]) * u.y, bad);
+                    o.z = f32_to_act16_noting(silu_f(acc[t][4 * b + 2]) * u.z, bad);
+                    o.w = f32_to_act16_noting(silu_f(acc[t][4 * b + 3]) * u.w, bad);
                     *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
                 }
             }
         }
+        report_saturation(g.sat_count, bad);
     }
 }
 
@@ -322,6 +363,7 @@ __global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
         if (c + i < NC) iter(st[i], c + i);
 
     // registers 4b..4b+3 hold tile rows 8b + 4*lh .. +3: b = 0, 1 are gate rows, b = 2, 3 the up rows 16 below
+    bool bad = false;
 #pragma unroll
     for (int t = 0; t < M32; ++t) {
         const int m = m0 + t * 32 + l32;
@@ -330,14 +372,15 @@ __global__ __launch_bounds__(64 * NW) void swiglu_stream_kernel(GemmArgs g) {
             const int fo = f_first + 8 * b + 4 * lh;
             if (m < g.M && fo < g.N) {
                 ushort4 o;
-                o.x = f32_to_act16(silu_f(acc[t][4 * b]) * acc[t][4 * b + 8]);
-                o.y = f32_to_act16(silu_f(acc[t][4 * b + 1]) * acc[t][4 * b + 9]);
-                o.z = f32_to_act16(silu_f(acc[t][4 * b + 2]) * acc[t][4 * b + 10]);
-                o.w = f32_to_act16(silu_f(acc[t][4 * b + 3]) * acc[t][4 * b + 11]);
+                o.x = f32_to_act16_noting(silu_f(acc[t][4 * b]) * acc[t][4 * b + 8], bad);
+                o.y = f32_to_act16_noting(silu_f(acc[t][4 * b + 1]) * acc[t][4 * b + 9], bad);
+                o.z = f32_to_act16_noting(silu_f(acc[t][4 * b + 2]) * acc[t][4 * b + 10], bad);
+                o.w = f32_to_act16_noting(silu_f(acc[t][4 * b + 3]) * acc[t][4 * b + 11], bad);
                 *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + fo) = o;
             }
         }
     }
+    report_saturation(g.sat_count, bad);
 }
 
 template <int M32, int NW, int PD>
@@ -365,7 +408,7 @@ static int swiglu_waves(int N, int m_tiles) {
 }
 
 template <int M32, int WN, bool SWIGLU, int PD>
-static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
+static hipError_t launch_one(const GemmArgs& a, hipStream_t s, bool sample = false) {
     GemmArgs g = a;
     g.m_tiles = (a.M + 32 * M32 - 1) / (32 * M32);
     const int cols = SWIGLU ? 16 * WN : 32 * WN;
@@ -373,7 +416,11 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
     size_t lds_bytes = (size_t)2 * 32 * M32 * 272;
     if (SWIGLU) lds_bytes = std::max(lds_bytes, (size_t)2 * M32 * 4 * 64 * sizeof(float4));
     else lds_bytes = std::max(lds_bytes, (size_t)4 * 32 * 144);       // the four waves' output staging tiles
-    if (!SWIGLU && a.wf)
+    if (sample) {
+        if (SWIGLU || !a.wf || g.splits != 1 || !a.s_part || a.s_tiles != n_tiles) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, false, PD, true, true>), dim3(n_tiles * g.m_tiles, 1), dim3(256),
+                           lds_bytes, s, g);
+    } else if (!SWIGLU && a.wf)
         hipLaunchKernelGGL((gemm_stream_kernel<M32, WN, false, PD, true>), dim3(n_tiles * g.m_tiles, g.splits), dim3(256),
                            lds_bytes, s, g);
     else
@@ -383,18 +430,21 @@ static hipError_t launch_one(const GemmArgs& a, hipStream_t s) {
 }
 
 template <bool SWIGLU>
-static hipError_t launch_shape(const GemmArgs& a, int bn, hipStream_t s) {
+static hipError_t launch_shape(const GemmArgs& a, int bn, hipStream_t s, bool sample = false) {
     // bn = weight rows per workgroup (128 or 64); narrower workgroups split the batch between waves
-    if (a.M <= 32) return launch_one<1, 4, SWIGLU, 4>(a, s);
-    if (a.M <= 64) return bn >= 128 ? launch_one<2, 4, SWIGLU, 3>(a, s) : launch_one<2, 2, SWIGLU, 3>(a, s);
+    if (a.M <= 32) return launch_one<1, 4, SWIGLU, 4>(a, s, sample);
+    if (a.M <= 64) return bn >= 128 ? launch_one<2, 4, SWIGLU, 3>(a, s, sample) : launch_one<2, 2, SWIGLU, 3>(a, s, sample);
 #ifndef STREAM_PD
 #define STREAM_PD 2
 #endif
 #ifndef SWIGLU_PD
 #define SWIGLU_PD 2
 #endif
-    return bn >= 128 ? launch_one<4, 4, SWIGLU, STREAM_PD>(a, s) : launch_one<4, 2, SWIGLU, 3>(a, s);
+    return bn >= 128 ? launch_one<4, 4, SWIGLU, STREAM_PD>(a, s, sample) : launch_one<4, 2, SWIGLU, 3>(a, s, sample);
 }
+
+// columns of the LM head that one workgroup of the sampling epilogue covers (host code sizes s_part with it)
+int gemm_sample_tile_cols(int M, int bn) { return (M > 32 && bn < 128) ? 64 : 128; }
 
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s) {
     if ((a.K & 127) || (a.N & 15) || a.splits < 1 || a.splits > (a.K >> 7)) return hipErrorInvalidValue;
@@ -410,7 +460,7 @@ hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream
         }
         return launch_shape<true>(a, bn, s);
     }
-    return launch_shape<false>(a, bn, s);
+    return launch_shape<false>(a, bn, s, epilogue == EPI_SAMPLE);
 }
 
 }  // namespace spiral

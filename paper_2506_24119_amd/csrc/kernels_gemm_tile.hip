@@ -182,6 +182,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
                 }
         }
     } else {
+        bool bad = false;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int m = m0 + wm * 128 + i * 32 + l32;
@@ -192,14 +193,15 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
                     const int f = n0 + (wn * J + j) * 16 + 8 * b + 4 * lh;
                     if (m < g.M && f < g.N) {
                         ushort4 o;
-                        o.x = f32_to_act16(silu_f(acc[j][i][4 * b]) * acc[j][i][4 * b + 8]);
-                        o.y = f32_to_act16(silu_f(acc[j][i][4 * b + 1]) * acc[j][i][4 * b + 9]);
-                        o.z = f32_to_act16(silu_f(acc[j][i][4 * b + 2]) * acc[j][i][4 * b + 10]);
-                        o.w = f32_to_act16(silu_f(acc[j][i][4 * b + 3]) * acc[j][i][4 * b + 11]);
+                        o.x = f32_to_act16_noting(silu_f(acc[j][i][4 * b]) * acc[j][i][4 * b + 8], bad);
+                        o.y = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 1]) * acc[j][i][4 * b + 9], bad);
+                        o.z = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 2]) * acc[j][i][4 * b + 10], bad);
+                        o.w = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 3]) * acc[j][i][4 * b + 11], bad);
                         *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
                     }
                 }
         }
+        report_saturation(g.sat_count, bad);
     }
 }
 

@@ -44,6 +44,40 @@ hipError_t launch_upload(int32_t* dev_dst, const int32_t* host_src, int n, hipSt
     return hipSuccess;
 }
 
+// several short host arrays in one launch: segment j of the packed chunk goes to dst[j]
+struct UploadPlan { int32_t* dst[4]; int32_t first[5]; };      // first[j] .. first[j + 1]: segment j inside the chunk
+__global__ void upload_multi_kernel(UploadPlan p, IntChunk c, int n) {
+    const int i = threadIdx.x;
+    if (i >= n) return;
+    int j = 0;
+    while (j < 3 && i >= p.first[j + 1]) ++j;
+    p.dst[j][i - p.first[j]] = c.v[i];
+}
+
+hipError_t launch_upload_multi(int32_t* const* dev_dst, const int32_t* const* host_src, const int* n, int n_seg, hipStream_t s) {
+    if (n_seg < 1 || n_seg > 4) return hipErrorInvalidValue;
+    int total = 0;
+    for (int j = 0; j < n_seg; ++j) total += n[j];
+    if (total > kUploadInts) {                       // too long for one chunk: one upload per array
+        for (int j = 0; j < n_seg; ++j) {
+            hipError_t e = launch_upload(dev_dst[j], host_src[j], n[j], s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
+    UploadPlan p;
+    IntChunk c;
+    int off = 0;
+    for (int j = 0; j < 4; ++j) {
+        p.first[j] = off;
+        p.dst[j] = j < n_seg ? dev_dst[j] : nullptr;
+        if (j < n_seg) { for (int i = 0; i < n[j]; ++i) c.v[off + i] = host_src[j][i]; off += n[j]; }
+    }
+    p.first[4] = off;
+    hipLaunchKernelGGL(upload_multi_kernel, dim3(1), dim3(kUploadInts), 0, s, p, c, total);
+    return hipGetLastError();
+}
+
 __global__ void scatter_kernel(int32_t* base, PairChunk c, int n) {
     int i = threadIdx.x;
     if (i < n) base[c.idx[i]] = c.val[i];
@@ -103,22 +137,8 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
 template <bool WBF16, bool ACT32>
 __global__ __launch_bounds__(256) void embed_norm_kernel(EmbedArgs a, RopeFreq f) {
     __shared__ float red[4];
-    __shared__ int s_pos;
     const int r = blockIdx.x;
-    if (a.decode) {
-        if (threadIdx.x == 0) {
-            const int seq = a.seq_ids[r];
-            const int pos = a.lens[seq];
-            a.lens[seq] = pos + 1;
-            a.row_seq[r] = seq;
-            a.row_pos[r] = pos;
-            s_pos = pos;
-        }
-    } else if (threadIdx.x == 0) {
-        s_pos = a.row_pos[r];
-    }
-    __syncthreads();
-    const int pos = s_pos;
+    const int pos = a.row_pos[r];
     if ((int)threadIdx.x < a.half_hd) {
         double ang = (double)pos * f.inv_freq[threadIdx.x];
         a.rope[(size_t)r * a.half_hd + threadIdx.x] = make_float2((float)cos(ang), (float)sin(ang));
@@ -194,6 +214,7 @@ __global__ __launch_bounds__(1024) void add_norm_wide_kernel(NormArgs a) {
     float tot = 0.f;
     for (int w = 0; w < n_waves; ++w) tot += red[w];
     const float rs = rsqrtf(tot / (float)a.d + a.eps);
+    bool bad = false;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int gidx = threadIdx.x + j * blockDim.x;
@@ -201,12 +222,13 @@ __global__ __launch_bounds__(1024) void add_norm_wide_kernel(NormArgs a) {
             const int i = gidx * 4;
             const float4 gn = *(const float4*)(a.gain + i);
             const size_t o = (size_t)ro * a.d + i;
-            ActStore<ACT32>::put(a.h, o, v[j].x * rs * gn.x);
-            ActStore<ACT32>::put(a.h, o + 1, v[j].y * rs * gn.y);
-            ActStore<ACT32>::put(a.h, o + 2, v[j].z * rs * gn.z);
-            ActStore<ACT32>::put(a.h, o + 3, v[j].w * rs * gn.w);
+            ActStore<ACT32>::put_noting(a.h, o, v[j].x * rs * gn.x, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 1, v[j].y * rs * gn.y, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 2, v[j].z * rs * gn.z, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 3, v[j].w * rs * gn.w, bad);
         }
     }
+    report_saturation(a.sat_count, bad);
 }
 
 template <bool ACT32>
@@ -226,8 +248,10 @@ __global__ __launch_bounds__(256) void add_norm_kernel(NormArgs a) {
     }
     ss = block_sum_256(ss, red);
     const float rs = rsqrtf(ss / (float)a.d + a.eps);
+    bool bad = false;
     for (int i = threadIdx.x; i < a.d; i += 256)
-        ActStore<ACT32>::put(a.h, (size_t)ro * a.d + i, x[i] * rs * a.gain[i]);
+        ActStore<ACT32>::put_noting(a.h, (size_t)ro * a.d + i, x[i] * rs * a.gain[i], bad);
+    report_saturation(a.sat_count, bad);
 }
 
 hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s) {
@@ -277,6 +301,7 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
         page_base = ((size_t)page * a.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * hd);
     }
 
+    bool bad = false;
     for (int p = lane; p < ((half + 63) & ~63); p += 64) {
         const bool act = p < half;
         float lo = 0.f, hi = 0.f;
@@ -310,22 +335,23 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
         }
         if (is_q) {
             uint16_t* q = a.q + ((size_t)r * a.n_q_heads + head) * hd;
-            q[p] = f32_to_act16(lo);
-            q[p + half] = f32_to_act16(hi);
+            q[p] = f32_to_act16_noting(lo, bad);
+            q[p + half] = f32_to_act16_noting(hi, bad);
         } else if (is_k) {
             // K element (token, d) sits at (d/32)*512 + (((d%32)/8)*16 + token)*8 + d%8
             uint16_t* K = a.pages + page_base;
             const int d0 = p, d1 = p + half;
-            K[(d0 >> 5) * 512 + ((((d0 & 31) >> 3) * 16 + slot) << 3) + (d0 & 7)] = f32_to_act16(lo);
-            K[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) * 16 + slot) << 3) + (d1 & 7)] = f32_to_act16(hi);
+            K[(d0 >> 5) * 512 + ((((d0 & 31) >> 3) * 16 + slot) << 3) + (d0 & 7)] = f32_to_act16_noting(lo, bad);
+            K[(d1 >> 5) * 512 + ((((d1 & 31) >> 3) * 16 + slot) << 3) + (d1 & 7)] = f32_to_act16_noting(hi, bad);
         } else {
             // V element (d, token) sits at (d/32)*512 + ((token/4)*16 + d%16)*8 + ((d/16)%2)*4 + token%4
             uint16_t* V = a.pages + page_base + (size_t)kPageTokens * hd;
             const int d0 = p, d1 = p + half;
-            V[(d0 >> 5) * 512 + ((((slot >> 2) * 16) + (d0 & 15)) << 3) + (((d0 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16(lo);
-            V[(d1 >> 5) * 512 + ((((slot >> 2) * 16) + (d1 & 15)) << 3) + (((d1 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16(hi);
+            V[(d0 >> 5) * 512 + ((((slot >> 2) * 16) + (d0 & 15)) << 3) + (((d0 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16_noting(lo, bad);
+            V[(d1 >> 5) * 512 + ((((slot >> 2) * 16) + (d1 & 15)) << 3) + (((d1 >> 4) & 1) << 2) + (slot & 3)] = f32_to_act16_noting(hi, bad);
         }
     }
+    report_saturation(a.sat_count, bad);
 }
 
 hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s) {
@@ -383,16 +409,6 @@ hipError_t launch_repack(const void* src0, const void* src1, const void* src2, i
 // One block of 1024 threads per row; every thread scans a strided slice, then a wave shuffle
 // reduction and a 16-entry LDS reduction pick the winner.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
-__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
-    return v > bv || (v == bv && i < bi);
-}
-
 __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int V, float temperature, int mode,
                                                       KeyChunk keys, const float* noise, int32_t* out) {
     // mode 0: greedy; 1: generated noise; 2: noise buffer
@@ -411,9 +427,7 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int V
             if (mode == 2) {
                 g = nr[v];
             } else {
-                const uint32_t r = (uint32_t)(mix64(key + (uint64_t)v * 0x9E3779B97F4A7C15ull) >> 32);
-                const float u = ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;   // 2^-23
-                g = -logf(-logf(u));
+                g = gumbel_noise(key, v);
             }
             sc = sc / temperature + g;      // IEEE division, as the definition states it
         }
@@ -448,6 +462,40 @@ hipError_t launch_sample(const float* logits, int B, int V, float temperature, c
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// Second half of the fused LM head + sampler: the winner among the per-tile (score, index) pairs of a row.
+__global__ __launch_bounds__(256) void sample_pick_kernel(const float2* part, int n_tiles, int32_t* out) {
+    __shared__ float s_v[4];
+    __shared__ int s_i[4];
+    const int row = blockIdx.x;
+    const float2* pr = part + (size_t)row * n_tiles;
+    float bv = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int t = threadIdx.x; t < n_tiles; t += 256) {
+        const float2 e = pr[t];
+        const int i = __float_as_int(e.y);
+        if (better(e.x, i, bv, bi)) { bv = e.x; bi = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { s_v[wave] = bv; s_i[wave] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (better(s_v[w], s_i[w], bv, bi)) { bv = s_v[w]; bi = s_i[w]; }
+        out[row] = bi == 0x7FFFFFFF ? 0 : bi;
+    }
+}
+
+hipError_t launch_sample_pick(const float2* part, int B, int n_tiles, int32_t* out, hipStream_t s) {
+    hipLaunchKernelGGL(sample_pick_kernel, dim3(B), dim3(256), 0, s, part, n_tiles, out);
+    return hipGetLastError();
 }
 
 }  // namespace spiral

@@ -18,12 +18,6 @@ namespace {
 constexpr int kThreads = 1024;
 constexpr int kWaves = kThreads / 64;
 
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
-
 // larger float <=> larger key; -0 and +0 share a key
 __device__ __forceinline__ uint32_t order_key(float z) {
     const uint32_t b = __float_as_uint(z + 0.0f);

@@ -57,6 +57,8 @@ struct Tune {
     int attn_stream = 1;           // 1: balanced page stream over the whole batch; 0: one workgroup per chunk
     int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
     int frag = 1;                  // 0: ignore spiral_model_repack (weights stay row-major; for A/B measurements)
+    int slice = 1;                 // 1: narrow projections keep their activation slice resident in LDS (gemm_slice_kernel)
+    int fail_after = 0;            // test hook: the n-th timed launch from now reports a launch failure instead of running
 };
 constexpr int kMaxSplit = 16;
 constexpr int kScoreSplits = 64;       // vocabulary ranges of the scoring pass (partial log-sum-exp pairs per row)
@@ -84,22 +86,18 @@ struct spiral_model {
 struct spiral_kv_pool {
     const spiral_model* m;
     int32_t* d_block_table;
-    int32_t* d_lens;
+    int32_t* d_status;                        // [0]: count of activations that left the 16-bit range
     uint16_t* d_pages;
     int n_pages, max_seqs, max_blocks;
     size_t layer_elems;                       // elements between consecutive layers' page arrays
     std::vector<int32_t> free_list;           // back = next page handed out
     std::vector<int32_t> h_lens;
     std::vector<std::vector<int32_t>> h_pages;
-    std::vector<int32_t> uploaded_ids;        // seq ids currently sitting in the workspace
-    const void* uploaded_ws = nullptr;
 };
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-static void parse_tune(Tune& t) {
-    const char* e = getenv("SPIRAL_TUNE");
-    if (!e) return;
+static void parse_tune(Tune& t, const char* e) {
     std::string s(e);
     size_t i = 0;
     while (i < s.size()) {
@@ -121,6 +119,8 @@ static void parse_tune(Tune& t) {
                 else if (k == "stream") { t.attn_stream = a; }
                 else if (k == "wgs") { t.attn_wgs = a; }
                 else if (k == "frag") { t.frag = a; }
+                else if (k == "slice") { t.slice = a; }
+                else if (k == "fail_after") { t.fail_after = a; }
             }
         }
         i = j + 1;
@@ -128,6 +128,16 @@ static void parse_tune(Tune& t) {
     auto clampi = [](int& v, int lo, int hi) { v = v < lo ? lo : (v > hi ? hi : v); };
     clampi(t.s_qkv, 0, kMaxSplit); clampi(t.s_o, 0, kMaxSplit); clampi(t.s_down, 0, kMaxSplit);
     clampi(t.chunk_pages, 1, 1 << 20);
+}
+
+extern "C" int spiral_model_tune(spiral_model* m, const char* spec) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "model_tune: null model");
+    if (!spec) return fail(SPIRAL_ERR_INVALID_ARG, "model_tune: null spec");
+    Tune t = m->tune;
+    parse_tune(t, spec);
+    if (t.frag != m->tune.frag && m->f_lm) return fail(SPIRAL_ERR_INVALID_ARG, "model_tune: frag must be set before spiral_model_repack");
+    m->tune = t;
+    return SPIRAL_OK;
 }
 
 extern "C" int spiral_model_load(const spiral_model_config* cfg, const void* const* host_dev_weights,
@@ -175,7 +185,6 @@ extern "C" int spiral_model_load(const spiral_model_config* cfg, const void* con
     m->w_bf16 = c.weight_dtype == SPIRAL_WEIGHT_BF16;
     for (int j = 0; j < 64; ++j)
         m->freq.inv_freq[j] = j < c.head_dim / 2 ? std::pow((double)c.rope_theta, -2.0 * j / c.head_dim) : 0.0;
-    parse_tune(m->tune);
     {
         // compute units of the current device (the stream attention kernel launches 3 workgroups on each);
         // without a device the default stays, model_load itself touches no GPU state
@@ -298,6 +307,7 @@ extern "C" int spiral_profile_end(spiral_model* m, double* host_total_ms, int* h
 // Runs one launch, bracketed by events when its class is being profiled.
 template <typename F>
 static hipError_t timed(spiral_model* m, int kclass, hipStream_t s, F&& launch) {
+    if (m->tune.fail_after > 0 && --m->tune.fail_after == 0) return hipErrorLaunchFailure;     // host-forced, nothing is launched
     Profiler& p = m->prof;
     const bool on = p.active && p.kclass == kclass && 2 * (p.used + 1) <= (int)p.ev.size();
     if (on) { hipError_t e = hipEventRecord(p.ev[2 * p.used], s); if (e != hipSuccess) return e; }
@@ -315,6 +325,7 @@ struct Workspace {
     float* attn_part; float2* rope;
     int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows, *page_start;
     float *score_part, *score_tgt;
+    uint64_t* s_keys; float2* s_part;         // fused sampler: row keys, per-tile winners
     size_t bytes;
 };
 
@@ -360,6 +371,8 @@ static Workspace carve(const spiral_model* m, char* base, int rows, int max_cont
     w.attn_part = (float*)take(brows * c.n_kv_heads * decode_slots(m, max_context) * G * (c.head_dim + 2) * 4);
     w.score_part = (float*)take(R * kScoreSplits * 8);
     w.score_tgt = (float*)take(R * 4);
+    w.s_keys = (uint64_t*)take(SPIRAL_MAX_BATCH * 8);
+    w.s_part = (float2*)take(brows * (size_t)((c.vocab + 63) / 64) * 8);
     w.bytes = off;
     return w;
 }
@@ -373,7 +386,7 @@ extern "C" size_t spiral_workspace_bytes(const spiral_model* m, int max_rows, in
 // KV pool
 // ---------------------------------------------------------------------------------------------
 static size_t pool_header_bytes(int max_seqs, int max_blocks) {
-    return align256((size_t)max_seqs * max_blocks * 4) + align256((size_t)max_seqs * 4);
+    return align256((size_t)max_seqs * max_blocks * 4) + 256;          // block table, status block
 }
 static size_t page_layer_elems(const spiral_model* m) {      // elements of one page in one layer
     return (size_t)m->cfg.n_kv_heads * 2 * kPageTokens * m->cfg.head_dim;
@@ -412,7 +425,7 @@ extern "C" int spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_
     p->m = m;
     char* base = (char*)dev_mem;
     p->d_block_table = (int32_t*)base;
-    p->d_lens = (int32_t*)(base + align256((size_t)max_seqs * max_blocks_per_seq * 4));
+    p->d_status = (int32_t*)(base + align256((size_t)max_seqs * max_blocks_per_seq * 4));
     p->d_pages = (uint16_t*)(base + pool_header_bytes(max_seqs, max_blocks_per_seq));
     p->n_pages = n_pages; p->max_seqs = max_seqs; p->max_blocks = max_blocks_per_seq;
     p->layer_elems = (size_t)n_pages * page_layer_elems(m);
@@ -426,6 +439,11 @@ extern "C" int spiral_kv_pool_create(const spiral_model* m, void* dev_mem, size_
 }
 
 extern "C" void spiral_kv_pool_free(spiral_kv_pool* p) { delete p; }
+
+extern "C" long long spiral_kv_pool_status_offset(const spiral_kv_pool* p) {
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "kv_pool_status_offset: null pool");
+    return (long long)((const char*)p->d_status - (const char*)p->d_block_table);
+}
 
 static int check_ids(const spiral_kv_pool* p, const int32_t* ids, int n, const char* who) {
     if (!ids) return fail(SPIRAL_ERR_INVALID_ARG, "%s: null sequence ids", who);
@@ -444,9 +462,7 @@ extern "C" int spiral_seq_reset(spiral_kv_pool* p, const int32_t* host_seq_ids, 
     if (n == 0) return SPIRAL_OK;
     int rc = check_ids(p, host_seq_ids, n, "seq_reset");
     if (rc) return rc;
-    std::vector<int32_t> idx(n), val(n, 0);
-    for (int i = 0; i < n; ++i) idx[i] = host_seq_ids[i];
-    HIP_TRY(launch_scatter(p->d_lens, idx.data(), val.data(), n, (hipStream_t)stream));
+    (void)stream;                              // lengths live on the host: nothing to enqueue
     for (int i = 0; i < n; ++i) {
         std::vector<int32_t>& pg = p->h_pages[host_seq_ids[i]];
         for (size_t k = pg.size(); k-- > 0;) p->free_list.push_back(pg[k]);
@@ -467,7 +483,7 @@ extern "C" int spiral_seq_truncate(spiral_kv_pool* p, const int32_t* host_seq_id
         if (host_new_lens[i] < 0 || host_new_lens[i] > p->h_lens[host_seq_ids[i]])
             return fail(SPIRAL_ERR_INVALID_ARG, "seq_truncate: length %d outside [0, %d] for sequence %d",
                         host_new_lens[i], p->h_lens[host_seq_ids[i]], host_seq_ids[i]);
-    HIP_TRY(launch_scatter(p->d_lens, host_seq_ids, host_new_lens, n, (hipStream_t)stream));
+    (void)stream;
     for (int i = 0; i < n; ++i) {
         std::vector<int32_t>& pg = p->h_pages[host_seq_ids[i]];
         const size_t keep = (size_t)(host_new_lens[i] + kPageTokens - 1) / kPageTokens;
@@ -489,8 +505,10 @@ extern "C" int spiral_kv_free_pages(const spiral_kv_pool* p) {
 }
 
 // Checks that every listed sequence can grow by add[i] tokens, then takes the pages and enqueues the
-// block-table updates.  Nothing is modified when the check fails.
-static int grow(spiral_kv_pool* p, const int32_t* ids, const int32_t* add, int n, hipStream_t s, const char* who) {
+// block-table updates.  Nothing is modified when the check fails.  `before` receives the page counts the
+// sequences had, for ungrow().
+static int grow(spiral_kv_pool* p, const int32_t* ids, const int32_t* add, int n, hipStream_t s, const char* who,
+                std::vector<size_t>& before) {
     size_t need_pages = 0;
     for (int i = 0; i < n; ++i) {
         const long long new_len = (long long)p->h_lens[ids[i]] + add[i];
@@ -502,10 +520,12 @@ static int grow(spiral_kv_pool* p, const int32_t* ids, const int32_t* add, int n
     if (need_pages > p->free_list.size())
         return fail(SPIRAL_ERR_OOM_KV, "%s: %zu pages needed, %zu free", who, need_pages, p->free_list.size());
     std::vector<int32_t> idx, val;
+    before.resize(n);
     for (int i = 0; i < n; ++i) {
         const int new_len = p->h_lens[ids[i]] + add[i];
         const size_t blocks = (size_t)(new_len + kPageTokens - 1) / kPageTokens;
         std::vector<int32_t>& pg = p->h_pages[ids[i]];
+        before[i] = pg.size();
         while (pg.size() < blocks) {
             const int32_t page = p->free_list.back();
             p->free_list.pop_back();
@@ -514,17 +534,28 @@ static int grow(spiral_kv_pool* p, const int32_t* ids, const int32_t* add, int n
             pg.push_back(page);
         }
     }
-    if (!idx.empty()) HIP_TRY(launch_scatter(p->d_block_table, idx.data(), val.data(), (int)idx.size(), s));
+    if (!idx.empty()) {
+        hipError_t e = launch_scatter(p->d_block_table, idx.data(), val.data(), (int)idx.size(), s);
+        if (e != hipSuccess) {
+            // nothing was enqueued for the failed chunk onwards; give the pages back
+            for (int i = n; i-- > 0;) {
+                std::vector<int32_t>& pg = p->h_pages[ids[i]];
+                while (pg.size() > before[i]) { p->free_list.push_back(pg.back()); pg.pop_back(); }
+            }
+            return fail(SPIRAL_ERR_HIP, "%s: block-table update: %s", who, hipGetErrorString(e));
+        }
+    }
     return SPIRAL_OK;
 }
 
-static int upload_ids(spiral_kv_pool* p, const Workspace& w, const void* ws, const int32_t* ids, int n, hipStream_t s) {
-    if (p->uploaded_ws == ws && (int)p->uploaded_ids.size() == n && std::equal(ids, ids + n, p->uploaded_ids.begin()))
-        return SPIRAL_OK;
-    HIP_TRY(launch_upload(w.seq_ids, ids, n, s));
-    p->uploaded_ids.assign(ids, ids + n);
-    p->uploaded_ws = ws;
-    return SPIRAL_OK;
+// Undoes grow() on the host after a later step of the same call failed: pages return to the free list in the
+// order they were taken from it, lengths were not advanced yet.  Block-table entries already written on the
+// device lie beyond the sequences' lengths and are overwritten by the next grow.
+static void ungrow(spiral_kv_pool* p, const int32_t* ids, int n, const std::vector<size_t>& before) {
+    for (int i = n; i-- > 0;) {
+        std::vector<int32_t>& pg = p->h_pages[ids[i]];
+        while (pg.size() > before[i]) { p->free_list.push_back(pg.back()); pg.pop_back(); }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -541,6 +572,9 @@ struct StepCtx {
     int total_units = 0, units_per_wg = 0, n_slots = 0;   // decode, stream kernel
     const int32_t* score_targets = nullptr;                // scoring pass: per-row targets and output
     float* score_out = nullptr;
+    bool sample = false;                                   // fused LM head + sampler (no logits written)
+    float temperature = 0.f;
+    int32_t* out_tokens = nullptr;
 };
 
 static int run_layers(StepCtx& c) {
@@ -571,10 +605,11 @@ static int run_layers(StepCtx& c) {
                 sh_down = shape(t.bn_down, t.s_down, d, cfg.ffn_dim);
     const int s_qkv = sh_qkv.splits, s_o = sh_o.splits, s_down = sh_down.splits;
     int pending = 0;            // projection partials waiting to be added to the residual
+    int32_t* sat = c.p->d_status;
 
     for (int l = 0; l < cfg.n_layers; ++l) {
         if (l > 0) {
-            NormArgs n = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_ATTN_NORM), c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps};
+            NormArgs n = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_ATTN_NORM), c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps, sat};
             HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(n, act32, c.s); }));
         }
         GemmArgs g = {};
@@ -588,7 +623,7 @@ static int run_layers(StepCtx& c) {
         QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
                           (const float*)m->lw(l, SPIRAL_W_Q_NORM), (const float*)m->lw(l, SPIRAL_W_K_NORM),
                           c.w.rope, c.w.row_seq, c.w.row_pos, c.p->d_block_table, c.w.q, pages,
-                          c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps};
+                          c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps, sat};
         HIP_TRY(timed(m, SPIRAL_K_QKV_POST, c.s, [&] { return launch_qkv_post(qa, m->w_bf16, c.s); }));
 
         AttnArgs aa = {};
@@ -615,7 +650,7 @@ static int run_layers(StepCtx& c) {
         go.wf = m->f_lm ? m->f_o[l] : nullptr;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_O, c.s, [&] { return launch_gemm(go, EPI_STORE_F32, m->w_bf16, sh_o.bn, c.s); }));
 
-        NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps};
+        NormArgs n2 = {c.w.x, c.w.proj, (const float*)m->lw(l, SPIRAL_W_MLP_NORM), c.w.h, nullptr, c.rows, c.rows, d, s_o, cfg.rms_eps, sat};
         HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(n2, act32, c.s); }));
 
         GemmArgs gu = {};
@@ -623,6 +658,7 @@ static int run_layers(StepCtx& c) {
         gu.rows[0] = cfg.ffn_dim; gu.rows[1] = cfg.ffn_dim;
         gu.M = c.rows; gu.N = cfg.ffn_dim; gu.K = d; gu.out = c.w.mlp; gu.splits = 1;
         gu.wf = m->f_lm ? m->f_gu[l] : nullptr;
+        gu.sat_count = sat;
         HIP_TRY(timed(m, SPIRAL_K_GEMM_GATE_UP, c.s, [&] { return launch_gemm(gu, EPI_SWIGLU, m->w_bf16, t.bn_gu, c.s); }));
 
         GemmArgs gd = {};
@@ -634,7 +670,7 @@ static int run_layers(StepCtx& c) {
     }
     if (c.score_out) {
         // scoring pass: final norm on every row, then the LM head fused with log-softmax and the target gather
-        NormArgs na = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps};
+        NormArgs na = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.h, nullptr, c.rows, c.rows, d, pending, cfg.rms_eps, sat};
         HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(na, act32, c.s); }));
         const int n_tiles = (cfg.vocab + 127) / 128;
         ScoreArgs sa = {};
@@ -647,12 +683,21 @@ static int run_layers(StepCtx& c) {
     }
     // final norm on one row per sequence, then the LM head
     NormArgs nf = {c.w.x, c.w.proj, (const float*)m->w[1], c.w.hf, c.decode ? nullptr : c.w.last_rows,
-                   c.rows, c.B, d, pending, cfg.rms_eps};
+                   c.rows, c.B, d, pending, cfg.rms_eps, sat};
     HIP_TRY(timed(m, SPIRAL_K_NORM, c.s, [&] { return launch_add_norm(nf, act32, c.s); }));
     GemmArgs gl = {};
     gl.A = c.w.hf; gl.w[0] = m->w[2]; gl.rows[0] = cfg.vocab;
     gl.M = c.B; gl.N = cfg.vocab; gl.K = d; gl.out = c.logits; gl.splits = 1;
     gl.wf = m->f_lm;
+    if (c.sample) {
+        // the LM head keeps the best (score, index) of each 128-column tile per row; a small kernel picks the winner
+        const int cols = gemm_sample_tile_cols(c.B, t.bn_lm);
+        gl.out = nullptr; gl.s_keys = c.w.s_keys; gl.s_part = c.w.s_part; gl.s_temperature = c.temperature;
+        gl.s_tiles = (cfg.vocab + cols - 1) / cols;
+        HIP_TRY(timed(m, SPIRAL_K_GEMM_LM_HEAD, c.s, [&] { return launch_gemm(gl, EPI_SAMPLE, m->w_bf16, t.bn_lm, c.s); }));
+        HIP_TRY(timed(m, SPIRAL_K_SAMPLE, c.s, [&] { return launch_sample_pick(c.w.s_part, c.B, gl.s_tiles, c.out_tokens, c.s); }));
+        return SPIRAL_OK;
+    }
     HIP_TRY(timed(m, SPIRAL_K_GEMM_LM_HEAD, c.s, [&] { return launch_gemm(gl, EPI_STORE_F32, m->w_bf16, t.bn_lm, c.s); }));
     return SPIRAL_OK;
 }
@@ -661,7 +706,7 @@ static int check_common(spiral_model* m, spiral_kv_pool* p, const void* toks, vo
     if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null model", who);
     if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null pool", who);
     if (p->m != m) return fail(SPIRAL_ERR_INVALID_ARG, "%s: pool belongs to another model", who);
-    if (!toks || !logits) return fail(SPIRAL_ERR_INVALID_ARG, "%s: null token or logits pointer", who);
+    if (!toks || !logits) return fail(SPIRAL_ERR_INVALID_ARG, "%s: null token or output pointer", who);
     if (!ws || ((uintptr_t)ws & 255)) return fail(SPIRAL_ERR_INVALID_ARG, "%s: workspace null or not 256-byte aligned", who);
     if ((uintptr_t)logits & 15) return fail(SPIRAL_ERR_INVALID_ARG, "%s: logits not 16-byte aligned", who);
     return SPIRAL_OK;
@@ -689,35 +734,37 @@ static int prefill_or_score(spiral_model* m, spiral_kv_pool* p, const int32_t* h
     const size_t need = carve(m, nullptr, (int)rows, max_ctx).bytes;
     if (ws_bytes < need) return fail(SPIRAL_ERR_OOM_KV, "prefill: workspace of %zu bytes given, %zu needed", ws_bytes, need);
     hipStream_t s = (hipStream_t)stream;
-    rc = grow(p, host_seq_ids, host_lens, B, s, "prefill");
+    std::vector<size_t> before;
+    rc = grow(p, host_seq_ids, host_lens, B, s, "prefill", before);
     if (rc) return rc;
 
     Workspace w = carve(m, (char*)dev_ws, (int)rows, max_ctx);
-    std::vector<int32_t> cu(B + 1), base(B), last(B), new_len(B), ids(host_seq_ids, host_seq_ids + B);
+    std::vector<int32_t> cu(B + 1), base(B), last(B), ids(host_seq_ids, host_seq_ids + B);
     cu[0] = 0;
     for (int i = 0; i < B; ++i) {
         cu[i + 1] = cu[i] + host_lens[i];
         base[i] = p->h_lens[ids[i]];
         last[i] = cu[i + 1] - 1;
-        new_len[i] = base[i] + host_lens[i];
     }
-    rc = upload_ids(p, w, dev_ws, ids.data(), B, s);
-    if (rc) return rc;
-    HIP_TRY(launch_upload(w.cu_rows, cu.data(), B + 1, s));
-    HIP_TRY(launch_upload(w.base_pos, base.data(), B, s));
-    HIP_TRY(launch_upload(w.last_rows, last.data(), B, s));
-    HIP_TRY(launch_scatter(p->d_lens, ids.data(), new_len.data(), B, s));
-    HIP_TRY(launch_prefill_meta(w.cu_rows, w.base_pos, w.seq_ids, B, (int)rows, w.row_seq, w.row_pos, s));
-    for (int i = 0; i < B; ++i) p->h_lens[ids[i]] = new_len[i];
-
-    EmbedArgs e = {dev_tokens_packed, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h, nullptr, nullptr,
-                   w.row_seq, w.row_pos, w.rope, (int)rows, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab,
-                   m->cfg.rms_eps, 0};
-    HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
-    StepCtx c = {m, p, w, s, (int)rows, B, false, max_new, 1, dev_logits};
-    c.score_targets = dev_targets;
-    c.score_out = dev_logp;
-    return run_layers(c);
+    // everything that can fail runs before the lengths advance; on failure the pages go back
+    auto enqueue = [&]() -> int {
+        int32_t* dst[4] = {w.seq_ids, w.cu_rows, w.base_pos, w.last_rows};
+        const int32_t* src[4] = {ids.data(), cu.data(), base.data(), last.data()};
+        const int cnt[4] = {B, B + 1, B, B};
+        HIP_TRY(launch_upload_multi(dst, src, cnt, 4, s));
+        HIP_TRY(launch_prefill_meta(w.cu_rows, w.base_pos, w.seq_ids, B, (int)rows, w.row_seq, w.row_pos, s));
+        EmbedArgs e = {dev_tokens_packed, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h,
+                       w.row_pos, w.rope, (int)rows, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps};
+        HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
+        StepCtx c = {m, p, w, s, (int)rows, B, false, max_new, 1, dev_logits};
+        c.score_targets = dev_targets;
+        c.score_out = dev_logp;
+        return run_layers(c);
+    };
+    rc = enqueue();
+    if (rc) { ungrow(p, host_seq_ids, B, before); return rc; }
+    for (int i = 0; i < B; ++i) p->h_lens[ids[i]] = base[i] + host_lens[i];
+    return SPIRAL_OK;
 }
 
 extern "C" int spiral_prefill(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, const int32_t* host_lens,
@@ -747,52 +794,126 @@ extern "C" int spiral_policy_objective(const float* dev_logp_new, const float* d
     return SPIRAL_OK;
 }
 
-extern "C" int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
-                                  const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float* dev_logits,
-                                  void* stream) {
-    int rc = check_common(m, p, dev_in_tokens, dev_ws, dev_logits, "decode_step");
-    if (rc) return rc;
-    rc = check_ids(p, host_seq_ids, B, "decode_step");
-    if (rc) return rc;
-    int max_ctx = 0;
-    for (int i = 0; i < B; ++i) max_ctx = std::max(max_ctx, p->h_lens[host_seq_ids[i]] + 1);
-    const size_t need = carve(m, nullptr, B, max_ctx).bytes;
-    if (ws_bytes < need) return fail(SPIRAL_ERR_OOM_KV, "decode_step: workspace of %zu bytes given, %zu needed", ws_bytes, need);
-    hipStream_t s = (hipStream_t)stream;
-    std::vector<int32_t> ones(B, 1);
-    rc = grow(p, host_seq_ids, ones.data(), B, s, "decode_step");
-    if (rc) return rc;
-    Workspace w = carve(m, (char*)dev_ws, B, max_ctx);
-    rc = upload_ids(p, w, dev_ws, host_seq_ids, B, s);
-    if (rc) return rc;
-    for (int i = 0; i < B; ++i) p->h_lens[host_seq_ids[i]] += 1;
-
-    EmbedArgs e = {dev_in_tokens, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h, w.seq_ids, p->d_lens,
-                   w.row_seq, w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps, 1};
-    HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
-    StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
-    if (m->tune.attn_stream) {
-        // page counts after this step's append, as a prefix sum over the rows of the call
-        std::vector<int32_t> start(B + 1, 0);
-        for (int i = 0; i < B; ++i) start[i + 1] = start[i] + (p->h_lens[host_seq_ids[i]] + kPageTokens - 1) / kPageTokens;
-        HIP_TRY(launch_upload(w.page_start, start.data(), B + 1, s));
-        const int wgs = m->tune.attn_wgs > 0 ? m->tune.attn_wgs : 3 * m->n_cus;
-        c.total_units = start[B] * m->cfg.n_kv_heads;
-        c.units_per_wg = std::max(m->tune.chunk_pages, (c.total_units + wgs - 1) / wgs);
-        c.n_slots = decode_slots(m, max_ctx);
-    }
-    return run_layers(c);
-}
-
-// ---------------------------------------------------------------------------------------------
-// sampling
-// ---------------------------------------------------------------------------------------------
 static uint64_t mix64_host(uint64_t z) {
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
     return z ^ (z >> 31);
 }
+// the generator key of (seed, sequence, step): see the sampler's description in spiral.h
+static uint64_t row_key(uint64_t seed, int32_t seq_id, int32_t step) {
+    const uint64_t k0 = mix64_host(seed ^ 0x9E3779B97F4A7C15ull);
+    return mix64_host(k0 + (((uint64_t)(uint32_t)seq_id << 32) | (uint64_t)(uint32_t)step));
+}
 
+struct SampleSpec { float temperature; uint64_t seed; const int32_t* host_steps; int32_t* dev_out_tokens; };
+
+// One decode step; with `sp` the LM head feeds the sampler directly and no logits are written.
+static int decode_impl(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B, const int32_t* dev_in_tokens,
+                       void* dev_ws, size_t ws_bytes, float* dev_logits, const SampleSpec* sp, void* stream, const char* who) {
+    int rc = check_ids(p, host_seq_ids, B, who);
+    if (rc) return rc;
+    if (sp) {
+        if (!(sp->temperature >= 0.f) || !std::isfinite(sp->temperature))
+            return fail(SPIRAL_ERR_INVALID_ARG, "%s: temperature must be finite and >= 0", who);
+        if (sp->temperature > 0.f) {
+            if (!sp->host_steps) return fail(SPIRAL_ERR_INVALID_ARG, "%s: steps are needed to generate noise", who);
+            for (int i = 0; i < B; ++i)
+                if (sp->host_steps[i] < 0) return fail(SPIRAL_ERR_INVALID_ARG, "%s: negative step", who);
+        }
+        if (!m->w_bf16 || !m->f_lm || (m->cfg.d_model & 127) || (m->cfg.vocab & 15))
+            return fail(SPIRAL_ERR_SHAPE, "%s: needs repacked 16-bit weights, d_model %% 128 == 0 and vocab %% 16 == 0", who);
+    }
+    int max_ctx = 0;
+    for (int i = 0; i < B; ++i) max_ctx = std::max(max_ctx, p->h_lens[host_seq_ids[i]] + 1);
+    const size_t need = carve(m, nullptr, B, max_ctx).bytes;
+    if (ws_bytes < need) return fail(SPIRAL_ERR_OOM_KV, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, need);
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<int32_t> ones(B, 1);
+    std::vector<size_t> before;
+    rc = grow(p, host_seq_ids, ones.data(), B, s, who, before);
+    if (rc) return rc;
+    Workspace w = carve(m, (char*)dev_ws, B, max_ctx);
+
+    // per-call host arrays, one by-value upload: sequence and position of every row, the prefix sum of the rows'
+    // page counts after this step's append, and (sampling) the rows' generator keys as pairs of 32-bit halves
+    std::vector<int32_t> pos(B), start(B + 1, 0), keys;
+    for (int i = 0; i < B; ++i) {
+        pos[i] = p->h_lens[host_seq_ids[i]];
+        start[i + 1] = start[i] + (pos[i] + 1 + kPageTokens - 1) / kPageTokens;
+    }
+    if (sp && sp->temperature > 0.f) {
+        keys.resize((size_t)2 * B);
+        for (int i = 0; i < B; ++i) {
+            const uint64_t k = row_key(sp->seed, host_seq_ids[i], sp->host_steps[i]);
+            keys[2 * i] = (int32_t)(uint32_t)k;
+            keys[2 * i + 1] = (int32_t)(uint32_t)(k >> 32);
+        }
+    }
+    auto enqueue = [&]() -> int {
+        int32_t* dst[4] = {w.row_seq, w.row_pos, w.page_start, (int32_t*)w.s_keys};
+        const int32_t* src[4] = {host_seq_ids, pos.data(), start.data(), keys.data()};
+        const int cnt[4] = {B, B, B + 1, (int)keys.size()};
+        HIP_TRY(launch_upload_multi(dst, src, cnt, keys.empty() ? 3 : 4, s));
+        EmbedArgs e = {dev_in_tokens, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h,
+                       w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps};
+        HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
+        StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
+        if (m->tune.attn_stream) {
+            const int wgs = m->tune.attn_wgs > 0 ? m->tune.attn_wgs : 3 * m->n_cus;
+            c.total_units = start[B] * m->cfg.n_kv_heads;
+            c.units_per_wg = std::max(m->tune.chunk_pages, (c.total_units + wgs - 1) / wgs);
+            c.n_slots = decode_slots(m, max_ctx);
+        }
+        if (sp) { c.sample = true; c.temperature = sp->temperature; c.out_tokens = sp->dev_out_tokens; }
+        return run_layers(c);
+    };
+    rc = enqueue();
+    if (rc) { ungrow(p, host_seq_ids, B, before); return rc; }
+    for (int i = 0; i < B; ++i) p->h_lens[host_seq_ids[i]] += 1;
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_decode_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                                  const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float* dev_logits,
+                                  void* stream) {
+    int rc = check_common(m, p, dev_in_tokens, dev_ws, dev_logits, "decode_step");
+    if (rc) return rc;
+    return decode_impl(m, p, host_seq_ids, B, dev_in_tokens, dev_ws, ws_bytes, dev_logits, nullptr, stream, "decode_step");
+}
+
+extern "C" int spiral_decode_sample_step(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                                         const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float temperature,
+                                         uint64_t seed, const int32_t* host_steps, int32_t* dev_out_tokens, void* stream) {
+    int rc = check_common(m, p, dev_in_tokens, dev_ws, (float*)dev_out_tokens, "decode_sample_step");
+    if (rc) return rc;
+    const SampleSpec sp = {temperature, seed, host_steps, dev_out_tokens};
+    return decode_impl(m, p, host_seq_ids, B, dev_in_tokens, dev_ws, ws_bytes, nullptr, &sp, stream, "decode_sample_step");
+}
+
+// Entry points for other translation units of the library: the workspace a decode step over the listed
+// sequences needs, and the step itself on a given workspace.
+int spiral_decode_workspace_need(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B, const char* who,
+                                 size_t* need) {
+    if (!m) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null model", who);
+    if (!p) return fail(SPIRAL_ERR_NOT_LOADED, "%s: null pool", who);
+    if (p->m != m) return fail(SPIRAL_ERR_INVALID_ARG, "%s: pool belongs to another model", who);
+    int rc = check_ids(p, host_seq_ids, B, who);
+    if (rc) return rc;
+    int max_ctx = 0;
+    for (int i = 0; i < B; ++i) max_ctx = std::max(max_ctx, p->h_lens[host_seq_ids[i]] + 1);
+    *need = carve(m, nullptr, B, max_ctx).bytes;
+    return SPIRAL_OK;
+}
+int spiral_decode_on_workspace(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B, const int32_t* dev_in_tokens,
+                               void* dev_ws, size_t ws_bytes, float* dev_logits, void* stream, const char* who) {
+    int rc = check_common(m, p, dev_in_tokens, dev_ws, dev_logits, who);
+    if (rc) return rc;
+    return decode_impl(m, p, host_seq_ids, B, dev_in_tokens, dev_ws, ws_bytes, dev_logits, nullptr, stream, who);
+}
+
+// ---------------------------------------------------------------------------------------------
+// sampling
+// ---------------------------------------------------------------------------------------------
 extern "C" int spiral_sample(const float* dev_logits, int B, int V, float temperature, uint64_t seed,
                              const int32_t* host_seq_ids, const int32_t* host_steps, const float* dev_noise,
                              int32_t* dev_out_tokens, void* stream) {
@@ -802,10 +923,9 @@ extern "C" int spiral_sample(const float* dev_logits, int B, int V, float temper
     std::vector<uint64_t> keys(B, 0);
     if (temperature > 0.f && !dev_noise) {
         if (!host_seq_ids || !host_steps) return fail(SPIRAL_ERR_INVALID_ARG, "sample: seq ids and steps are needed to generate noise");
-        const uint64_t k0 = mix64_host(seed ^ 0x9E3779B97F4A7C15ull);
         for (int i = 0; i < B; ++i) {
             if (host_seq_ids[i] < 0 || host_steps[i] < 0) return fail(SPIRAL_ERR_INVALID_ARG, "sample: negative seq id or step");
-            keys[i] = mix64_host(k0 + (((uint64_t)(uint32_t)host_seq_ids[i] << 32) | (uint64_t)(uint32_t)host_steps[i]));
+            keys[i] = row_key(seed, host_seq_ids[i], host_steps[i]);
         }
     }
     HIP_TRY(launch_sample(dev_logits, B, V, temperature, keys.data(), temperature > 0.f ? dev_noise : nullptr,
@@ -828,10 +948,9 @@ extern "C" int spiral_sample_truncated(const float* dev_logits, int B, int V, fl
     std::vector<uint64_t> keys(B, 0);
     if (!dev_noise) {
         if (!host_seq_ids || !host_steps) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: seq ids and steps are needed to generate noise");
-        const uint64_t k0 = mix64_host(seed ^ 0x9E3779B97F4A7C15ull);
         for (int i = 0; i < B; ++i) {
             if (host_seq_ids[i] < 0 || host_steps[i] < 0) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: negative seq id or step");
-            keys[i] = mix64_host(k0 + (((uint64_t)(uint32_t)host_seq_ids[i] << 32) | (uint64_t)(uint32_t)host_steps[i]));
+            keys[i] = row_key(seed, host_seq_ids[i], host_steps[i]);
         }
     }
     HIP_TRY(launch_sample_truncated(dev_logits, B, V, temperature, top_k, top_p < 1.f ? top_p : 1.f, keys.data(), dev_noise,

@@ -7,6 +7,13 @@
 
 #include "spiral.h"
 
+// host-side hooks shared by the library's translation units (defined with the C ABI's host code)
+int spiral_set_error(int code, const char* text);
+int spiral_decode_workspace_need(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B, const char* who,
+                                 size_t* need);
+int spiral_decode_on_workspace(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B, const int32_t* dev_in_tokens,
+                               void* dev_ws, size_t ws_bytes, float* dev_logits, void* stream, const char* who);
+
 namespace spiral {
 
 // ---------------------------------------------------------------------------------------------
@@ -22,7 +29,7 @@ namespace spiral {
 
 constexpr int kPageTokens = 16;
 constexpr int kMaxGroup = 16;          // q heads per kv head handled by one attention tile
-constexpr int kUploadInts = 256;       // ints carried by value in one upload launch
+constexpr int kUploadInts = 768;       // ints carried by value in one upload launch (3 KB of kernel arguments)
 
 struct IntChunk { int32_t v[kUploadInts]; };
 struct PairChunk { int32_t idx[kUploadInts / 2]; int32_t val[kUploadInts / 2]; };
@@ -31,7 +38,9 @@ struct RopeFreq { double inv_freq[64]; };   // theta^(-2j/hd), j < hd/2 <= 64
 
 // GEMM: out[m][n] = sum_k A[m][k] * W[n][k]; W is up to three row blocks stacked along n
 // (q|k|v) or, for the SwiGLU epilogue, the gate and up matrices addressed by the same row.
-enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_SWIGLU = 1 };
+// EPI_SAMPLE (LM head only): no logits are written; every workgroup reduces its 128 vocabulary columns to the
+// best (score, index) per batch row, score = logit / T + Gumbel noise (or the logit itself when greedy).
+enum GemmEpilogue { EPI_STORE_F32 = 0, EPI_SWIGLU = 1, EPI_SAMPLE = 2 };
 
 struct GemmArgs {
     const void* A;        // activations [M][K] (act type)
@@ -42,6 +51,12 @@ struct GemmArgs {
     void* out;            // STORE_F32: fp32 [splits][M][N]; SWIGLU: act [M][N]
     int32_t splits;       // grid split of K (STORE_F32 only)
     int32_t m_tiles;      // ceil(M / rows per tile)
+    // EPI_SAMPLE: per-row generator keys (device), temperature (0: greedy), partial winners [M][s_tiles] (score, index bits)
+    const uint64_t* s_keys;
+    float2* s_part;
+    float s_temperature;
+    int32_t s_tiles;
+    int32_t* sat_count;   // or null: incremented when an activation left the half-precision range (SwiGLU output)
 };
 
 struct AttnArgs {
@@ -62,6 +77,7 @@ struct AttnArgs {
 // Launchers (defined in the kernel translation units).  All enqueue on `s` and return the launch status.
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_upload(int32_t* dev_dst, const int32_t* host_src, int n, hipStream_t s);
+hipError_t launch_upload_multi(int32_t* const* dev_dst, const int32_t* const* host_src, const int* n, int n_seg, hipStream_t s);
 hipError_t launch_scatter(int32_t* dev_base, const int32_t* host_idx, const int32_t* host_val, int n, hipStream_t s);
 hipError_t launch_prefill_meta(const int32_t* cu_rows, const int32_t* base_pos, const int32_t* seq_ids, int B,
                                int n_rows, int32_t* row_seq, int32_t* row_pos, hipStream_t s);
@@ -72,14 +88,10 @@ struct EmbedArgs {
     const float* gain;        // [d]
     float* x;                 // [rows][d]
     void* h;                  // act [rows][d]
-    const int32_t* seq_ids;   // decode: [rows]; prefill: null
-    int32_t* lens;            // decode: device lengths, read then incremented
-    int32_t* row_seq;         // decode: written; prefill: read-only (already built)
-    int32_t* row_pos;
-    float2* rope;             // [rows][hd/2] (cos, sin)
+    const int32_t* row_pos;   // [rows] position of each row's token
+    float2* rope;             // [rows][hd/2] (cos, sin), written
     int32_t n_rows, d, half_hd, vocab;
     float eps;
-    int32_t decode;
 };
 hipError_t launch_embed_norm(const EmbedArgs& a, const RopeFreq& f, bool w_bf16, bool act32, hipStream_t s);
 
@@ -91,6 +103,7 @@ struct NormArgs {
     const int32_t* row_map;   // null, or [rows_out] source row of each output row
     int32_t rows_in, rows_out, d, n_part;
     float eps;
+    int32_t* sat_count;       // or null
 };
 hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s);
 
@@ -105,6 +118,7 @@ struct QkvPostArgs {
     uint16_t* pages;          // this layer's pages
     int32_t n_rows, n_part, n_q_heads, n_kv_heads, hd, max_blocks;
     float eps;
+    int32_t* sat_count;       // or null
 };
 hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s);
 
@@ -118,6 +132,8 @@ hipError_t launch_attn_stream(const AttnArgs& a, int hd, bool act32, hipStream_t
 hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s);
 
+hipError_t launch_sample_pick(const float2* part, int B, int n_tiles, int32_t* out, hipStream_t s);
+int gemm_sample_tile_cols(int M, int bn);     // LM-head columns per workgroup of the sampling epilogue
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,
                          const float* noise, int32_t* out, hipStream_t s);
 // Fragment order of a 16-bit weight matrix [N][K] (N padded to a multiple of 32, K % 16 == 0): 1 KB blocks
@@ -157,11 +173,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {       // round t
     return (uint16_t)(u >> 16);
 }
 
-__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {        // round to nearest even, saturating
-    f = fminf(fmaxf(f, -65504.0f), 65504.0f);
-    _Float16 h = (_Float16)f;
+// round to nearest even; finite values beyond the half range saturate at +-65504, NaN stays NaN
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f) {
+    const float c = fminf(fmaxf(f, -65504.0f), 65504.0f);      // fmin/fmax drop a NaN operand: put it back
+    _Float16 h = (_Float16)(f != f ? f : c);
     return __builtin_bit_cast(uint16_t, h);
 }
+// true when f32_to_f16_bits(f) is not a rounding of f: saturated, infinite or NaN
+__device__ __forceinline__ bool f16_out_of_range(float f) { return !(fabsf(f) <= 65504.0f); }
 
 __device__ __forceinline__ uint16_t f32_to_act16(float f) {
 #if SPIRAL_ACT_F16
@@ -171,15 +190,48 @@ __device__ __forceinline__ uint16_t f32_to_act16(float f) {
 #endif
 }
 
+// conversion that also notes a value the 16-bit format cannot hold (callers report it through the pool's counter)
+__device__ __forceinline__ uint16_t f32_to_act16_noting(float f, bool& bad) {
+#if SPIRAL_ACT_F16
+    bad = bad || f16_out_of_range(f);
+#else
+    bad = bad || !(fabsf(f) <= 3.3895314e38f);
+#endif
+    return f32_to_act16(f);
+}
+// one increment per lane that saw an unrepresentable value (rare: the branch is normally not taken)
+__device__ __forceinline__ void report_saturation(int32_t* counter, bool bad) {
+    if (counter && bad) atomicAdd(counter, 1);
+}
+
 template <bool ACT32> struct ActStore;
 template <> struct ActStore<true> {
     typedef float type;
     static __device__ __forceinline__ void put(void* base, size_t i, float v) { ((float*)base)[i] = v; }
+    static __device__ __forceinline__ void put_noting(void* base, size_t i, float v, bool&) { ((float*)base)[i] = v; }
 };
 template <> struct ActStore<false> {
     typedef uint16_t type;
     static __device__ __forceinline__ void put(void* base, size_t i, float v) { ((uint16_t*)base)[i] = f32_to_act16(v); }
+    static __device__ __forceinline__ void put_noting(void* base, size_t i, float v, bool& bad) {
+        ((uint16_t*)base)[i] = f32_to_act16_noting(v, bad);
+    }
 };
+
+// ---- the sampler's counter generator (same stream in every kernel that draws noise)
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+// standard Gumbel noise of vocabulary entry v under a row key: u = ((r >> 9) + 0.5) * 2^-23, g = -ln(-ln u)
+__device__ __forceinline__ float gumbel_noise(uint64_t key, int v) {
+    const uint32_t r = (uint32_t)(mix64(key + (uint64_t)v * 0x9E3779B97F4A7C15ull) >> 32);
+    const float u = ((float)(r >> 9) + 0.5f) * 1.1920928955078125e-07f;   // 2^-23
+    return -logf(-logf(u));
+}
+// argmax order: larger score wins, equal scores go to the lower index
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) { return v > bv || (v == bv && i < bi); }
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll

@@ -46,10 +46,10 @@ def assert_tokens_match(got: np.ndarray, want: np.ndarray, margins: np.ndarray, 
     return int(sel.sum())
 
 
-def make_session(sb, g, w_host, n_pages, max_seqs, max_blocks, max_rows, max_context, page_seed=None):
+def make_session(sb, g, w_host, n_pages, max_seqs, max_blocks, max_rows, max_context, page_seed=None, tune=None):
     order = None if page_seed is None else si.make_page_order(n_pages, page_seed)
     return sb.Session(g, sb.weights_to_device(w_host), n_pages, max_seqs, max_blocks, max_rows, max_context,
-                      page_order=order)
+                      page_order=order, tune=tune)
 
 
 def run_teacher_forced(sb, sess, g, prompts, forced, temperature=0.0, seed=0, noise=None):
@@ -174,12 +174,10 @@ def test_long_context_spans_several_attention_chunks(sb):
 @pytest.mark.parametrize("tune", ["stream=0", "stream=0,chunk=1", "stream=1,chunk=1,wgs=7", "stream=1,chunk=2,wgs=100000",
                                   "stream=1,chunk=64,wgs=3"])
 @pytest.mark.parametrize("name", ["g4-qknorm", "g7-bias"])
-def test_decode_attention_launch_shapes(sb, name, tune, monkeypatch):
+def test_decode_attention_launch_shapes(sb, name, tune):
     """The decode attention in every decomposition the library can choose: one workgroup per chunk of
     pages, and the balanced page stream with workgroup ranges that cut (row, kv head) pairs at
-    arbitrary pages, hold many pairs, or hold one page each.  The library reads SPIRAL_TUNE when a
-    model is loaded."""
-    monkeypatch.setenv("SPIRAL_TUNE", tune)
+    arbitrary pages, hold many pairs, or hold one page each (spiral_model_tune selects them)."""
     g = SMALL[name]
     w = si.make_weights(g, seed=23)
     B, steps = 5, 18
@@ -188,7 +186,7 @@ def test_decode_attention_launch_shapes(sb, name, tune, monkeypatch):
     prompts[1] = np.resize(prompts[1], 15)                      # the first decode step fills the page exactly
     prompts[2] = np.resize(prompts[2], 16)                      # the first decode step opens a new page
     forced = si.make_forced_tokens(g.vocab, B, steps, seed=12)
-    sess = make_session(sb, g, w, n_pages=64, max_seqs=8, max_blocks=8, max_rows=512, max_context=128, page_seed=4)
+    sess = make_session(sb, g, w, n_pages=64, max_seqs=8, max_blocks=8, max_rows=512, max_context=128, page_seed=4, tune=tune)
     got_logits, _ = run_teacher_forced(sb, sess, g, prompts, forced)
     for b in range(B):
         want = oracle_teacher_forced(g, w, prompts[b], forced[:, b])
@@ -196,7 +194,7 @@ def test_decode_attention_launch_shapes(sb, name, tune, monkeypatch):
     sess.close()
 
 
-def test_repacked_weights_give_bit_identical_logits(sb, monkeypatch):
+def test_repacked_weights_give_bit_identical_logits(sb):
     """spiral_model_repack changes where the weight bytes sit and nothing else: prefill (small and large
     row counts), decode and the scoring pass return the same bits with and without it."""
     torch = _torch()
@@ -206,8 +204,7 @@ def test_repacked_weights_give_bit_identical_logits(sb, monkeypatch):
     forced = si.make_forced_tokens(g.vocab, 6, 5, seed=16)
     outs = []
     for tune in ("frag=0", "frag=1"):
-        monkeypatch.setenv("SPIRAL_TUNE", tune)
-        sess = make_session(sb, g, w, n_pages=96, max_seqs=8, max_blocks=16, max_rows=2048, max_context=256, page_seed=9)
+        sess = make_session(sb, g, w, n_pages=96, max_seqs=8, max_blocks=16, max_rows=2048, max_context=256, page_seed=9, tune=tune)
         assert (sess.repacked is not None)
         logits, _ = run_teacher_forced(sb, sess, g, prompts, forced)
         toks = torch.from_numpy(np.concatenate(prompts).astype(np.int32)).cuda()
