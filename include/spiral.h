@@ -195,6 +195,22 @@ int spiral_decode_sample_step(spiral_model* m, spiral_kv_pool* p, const int32_t*
                               const int32_t* dev_in_tokens, void* dev_ws, size_t ws_bytes, float temperature,
                               uint64_t seed, const int32_t* host_steps, int32_t* dev_out_tokens, void* stream);
 
+/* ---- decode step without a workspace argument --------------------------------------------------
+ * For callers that cannot allocate device memory or carry a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same step, same kernels and same results as
+ * spiral_decode_step, but the workspace is the library's own scratch memory: a device array of
+ * SPIRAL_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the process ends.  Neither
+ * this call nor anything it calls allocates or frees device memory.  A step that needs more
+ * (spiral_workspace_bytes(m, B, longest context + 1) > spiral_static_workspace_bytes()) is rejected with
+ * SPIRAL_ERR_OOM_KV and a message that says so; nothing is modified then.  All calls on one GPU share that
+ * GPU's array: calls that overlap on one GPU (two streams, two threads, two models) race; calls in stream
+ * order do not, and nothing has to be cleared between them (every part of the workspace a step reads it has
+ * written before).  Other errors as spiral_decode_step. */
+#define SPIRAL_STATIC_WORKSPACE_BYTES (16u << 20)
+size_t spiral_static_workspace_bytes(void);
+int spiral_decode_step_static(spiral_model* m, spiral_kv_pool* p, const int32_t* host_seq_ids, int B,
+                              const int32_t* dev_in_tokens, float* dev_logits, void* stream);
+
 /* ---- scoring pass (learner side) ---------------------------------------------------------------
  * The policy update of the paper (Alg. 1, last step; policy-gradient equation of Sec. 3) weights
  * log pi_theta(y_t | s_t) of every generated token with the RAE advantage of the player who produced it.

@@ -30,6 +30,7 @@ EXPORTS = [
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
     "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free", "spiral_model_tune", "spiral_kv_pool_status_offset", "spiral_decode_sample_step",
+    "spiral_decode_step_static", "spiral_static_workspace_bytes",
 ]
 
 
@@ -104,6 +105,10 @@ def load_library(path: Optional[str] = None):
     lib.spiral_decode_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, f32p, vp]
     lib.spiral_decode_sample_step.restype = C.c_int
     lib.spiral_decode_sample_step.argtypes = [vp, vp, i32p, C.c_int, vp, vp, C.c_size_t, C.c_float, C.c_uint64, i32p, vp, vp]
+    lib.spiral_decode_step_static.restype = C.c_int
+    lib.spiral_decode_step_static.argtypes = [vp, vp, i32p, C.c_int, vp, f32p, vp]
+    lib.spiral_static_workspace_bytes.restype = C.c_size_t
+    lib.spiral_static_workspace_bytes.argtypes = []
     lib.spiral_model_tune.restype = C.c_int
     lib.spiral_model_tune.argtypes = [vp, C.c_char_p]
     lib.spiral_kv_pool_status_offset.restype = C.c_longlong
@@ -274,6 +279,16 @@ def spiral_decode_sample_step(model: int, pool: int, seq_ids, dev_in_tokens, dev
                                                     0 if dev_ws is None else dev_ws.numel() * dev_ws.element_size(),
                                                     C.c_float(temperature), C.c_uint64(seed), _ip(st), _ptr(dev_out_tokens),
                                                     _stream_handle(stream)))
+
+
+def spiral_decode_step_static(model: int, pool: int, seq_ids, dev_in_tokens, dev_logits, stream=None):
+    ids = _i32(seq_ids)
+    _check(load_library().spiral_decode_step_static(model, pool, _ip(ids), int(ids.shape[0]), _ptr(dev_in_tokens),
+                                                    _ptr(dev_logits), _stream_handle(stream)))
+
+
+def spiral_static_workspace_bytes() -> int:
+    return load_library().spiral_static_workspace_bytes()
 
 
 def spiral_model_tune(model: int, spec: str):

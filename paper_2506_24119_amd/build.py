@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspiral.so")
-SOURCES = ["spiral_api.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_gemm_stream.hip", "kernels_gemm_tile.hip", "kernels_attn.hip", "kernels_sample.hip", "kernels_score.hip", "spiral_rae.cpp"]
+SOURCES = ["spiral_api.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_gemm_stream.hip", "kernels_gemm_tile.hip", "kernels_attn.hip", "kernels_sample.hip", "kernels_score.hip", "spiral_static_ws.hip", "spiral_rae.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
