@@ -75,14 +75,19 @@ def prefill_all(sess, prompts, group_tokens):
     return logits
 
 
-def run_steps(sess, sb, ids, logits, tokens, first_step, n, temperature, seed):
-    """n free-running steps: decode the current tokens, sample the next ones."""
+def run_steps(sess, sb, ids, logits, tokens, first_step, n, temperature, seed, fused=True):
+    """n free-running steps: decode the current tokens, sample the next ones.  fused: one call per step
+    (spiral_decode_sample_step: the LM head feeds the sampler, no logits are written); otherwise
+    spiral_decode_step + spiral_sample through the [B, vocab] logits."""
     B = len(ids)
     step_arr = np.empty(B, dtype=np.int32)
     for k in range(n):
-        sess.decode_step(ids, tokens, logits)
         step_arr.fill(first_step + k)
-        sess.sample(logits, temperature, seed, ids, step_arr, tokens)
+        if fused:
+            sess.decode_sample_step(ids, tokens, temperature, seed, step_arr, tokens)
+        else:
+            sess.decode_step(ids, tokens, logits)
+            sess.sample(logits, temperature, seed, ids, step_arr, tokens)
 
 
 def algorithmic_bytes(g, lens_after_append, B):

@@ -117,8 +117,8 @@ int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* s
  * spec is a comma-separated list of key=value items (unknown keys are ignored): "qkv=R:S", "o=R:S", "down=R:S"
  * (weight rows per workgroup : K splits of that projection), "gu=R", "lm=R", "chunk=P" (least pages per
  * attention workgroup), "stream=0|1" (decode attention as one balanced page stream, or one workgroup per chunk
- * of P pages), "wgs=N" (workgroups of the stream kernel), "frag=0|1" (use the repacked weights), "slice=0|1"
- * (narrow projections with the activation slice resident in LDS), "fail_after=N" (error-path tests: the N-th
+ * of P pages), "wgs=N" (workgroups of the stream kernel), "frag=0|1" (use the repacked weights),
+ * "fail_after=N" (error-path tests: the N-th
  * kernel launch of the layer stack from now on is not made and reports a launch failure).  Results stay within
  * the parity tolerance for every setting; the defaults are the measured best.  "frag" must be set before
  * spiral_model_repack, the others at any time between calls.  Errors: NOT_LOADED, INVALID_ARG. */

@@ -57,7 +57,6 @@ struct Tune {
     int attn_stream = 1;           // 1: balanced page stream over the whole batch; 0: one workgroup per chunk
     int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
     int frag = 1;                  // 0: ignore spiral_model_repack (weights stay row-major; for A/B measurements)
-    int slice = 1;                 // 1: narrow projections keep their activation slice resident in LDS (gemm_slice_kernel)
     int fail_after = 0;            // test hook: the n-th timed launch from now reports a launch failure instead of running
 };
 constexpr int kMaxSplit = 16;
@@ -119,7 +118,6 @@ static void parse_tune(Tune& t, const char* e) {
                 else if (k == "stream") { t.attn_stream = a; }
                 else if (k == "wgs") { t.attn_wgs = a; }
                 else if (k == "frag") { t.frag = a; }
-                else if (k == "slice") { t.slice = a; }
                 else if (k == "fail_after") { t.fail_after = a; }
             }
         }
