@@ -1,14 +1,22 @@
 #!/usr/bin/env python3
 """Decode-throughput benchmark of the self-play generation path on one MI355X.
 
-    python bench.py --gpus 1 --steps K --warmup W [--workload C3]
+    python bench.py --gpus 1 --steps K --warmup W [--workload C3] [--repeats 3]
 
-A "step" is one pass of the whole hot path over the batch: spiral_decode_step (embedding, all
-layers, LM head) followed by spiral_sample, free-running (each step consumes the tokens the
-previous step sampled).  Inputs (random-init weights, uniform-random prompts, shuffled physical
-pages) are synthetic, seeded and resident in HBM before the timed region; prefill is outside it.
-Prints ONE JSON line: generated tokens/s, plus the roofline of the dominant kernel (split-K paged
-decode attention) measured with HIP events, and the CPU oracle timed on the host as a baseline.
+A "step" is one pass of the whole hot path over the batch: one spiral_decode_sample_step (embedding, all
+layers, LM head feeding the Gumbel-max sampler), free-running (each step consumes the tokens the previous
+step sampled).  Inputs (random-init weights, uniform-random prompts, shuffled physical pages) are synthetic,
+seeded and resident in HBM before the timed region; prefill is outside it.
+
+Timed region: the workload is the configuration's whole decode run (C3: 512 steps).  When K is smaller than
+that, the K timed steps are the window in the middle of the run (steps [P, P + K), P = (run - K) // 2, reached
+by untimed steps), so that the context lengths are the run's mean ones rather than its shortest; K equal to
+the run length times all of it.  The window is timed `--repeats` times (state rewound with
+spiral_seq_truncate, W untimed warm-up steps before each) and the median is reported.
+
+Prints ONE JSON line: generated tokens/s; `roofline` for the dominant kernel (paged decode attention, HIP
+events around every launch) plus the whole step's fraction of peak HBM bandwidth and of a streaming read
+measured in the same run; `cpu_baseline`, the oracle timed on the host.
 """
 from __future__ import annotations
 
@@ -25,14 +33,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-PMC_TRAFFIC_OVER_ALGORITHMIC = 1.032      # measured ratio for the decode attention kernel (see profiles/)
+MFMA_PEAK_TFLOPS = 2500.0          # dense 16-bit MFMA peak of MI355X
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "attn_decode_c3_pmc_traffic.json")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_session(wl, total_new_tokens, prefill_group_tokens):
+def build_session(wl, total_new_tokens, prefill_group_tokens, tune=None):
     import torch
     from paper_2506_24119_amd import binding as sb
     from paper_2506_24119_amd import inputs as si
@@ -54,7 +63,7 @@ def build_session(wl, total_new_tokens, prefill_group_tokens):
     max_blocks = int(blocks.max())
     max_rows = max(wl.batch, min(int(lens.sum()), prefill_group_tokens + int(lens.max())))
     sess = sb.Session(g, w, n_pages, wl.batch, max_blocks, max_rows, int(final.max()),
-                      page_order=si.make_page_order(n_pages, wl.seed), device=dev)
+                      page_order=si.make_page_order(n_pages, wl.seed), device=dev, tune=tune)
     return sess, prompts, lens
 
 
@@ -75,7 +84,7 @@ def prefill_all(sess, prompts, group_tokens):
     return logits
 
 
-def run_steps(sess, sb, ids, logits, tokens, first_step, n, temperature, seed, fused=True):
+def run_steps(sess, ids, logits, tokens, first_step, n, temperature, seed, fused):
     """n free-running steps: decode the current tokens, sample the next ones.  fused: one call per step
     (spiral_decode_sample_step: the LM head feeds the sampler, no logits are written); otherwise
     spiral_decode_step + spiral_sample through the [B, vocab] logits."""
@@ -90,19 +99,16 @@ def run_steps(sess, sb, ids, logits, tokens, first_step, n, temperature, seed, f
             sess.sample(logits, temperature, seed, ids, step_arr, tokens)
 
 
-def algorithmic_bytes(g, lens_after_append, B):
-    """Bytes one decode step must move: weights of all layers + LM head, the whole KV context read
-    once per layer, the appended K/V, and the logits written and read back by the sampler."""
+def algorithmic_bytes(g, lens_after_append, B, fused):
+    """Bytes one decode step must move: weights of all layers + LM head, the whole KV context read once per
+    layer, the appended K/V, and - only when the sampler is a separate call - the logits written and read back."""
     wbytes = 2 if g.weight_dtype == 1 else 4
     weights = (g.n_layers * g.params_per_layer() + g.vocab * g.d_model) * wbytes
     kv_tok = 2 * g.n_kv_heads * g.head_dim * 2                      # K+V bytes per token per layer (16-bit cache)
     kv_read = int(lens_after_append.sum()) * kv_tok * g.n_layers
     kv_write = B * kv_tok * g.n_layers
-    logits = 2 * B * g.vocab * 4
+    logits = 0 if fused else 2 * B * g.vocab * 4
     return weights + kv_read + kv_write + logits, kv_read // g.n_layers
-
-
-MFMA_PEAK_TFLOPS = 2500.0          # dense 16-bit MFMA peak of MI355X
 
 
 def prefill_report(g, prompts, seconds, score):
@@ -121,7 +127,7 @@ def prefill_report(g, prompts, seconds, score):
 def next_rows(sess, sb, wl, prompts, ids, logits, group_tokens):
     """Measurements of the rows built beyond the decode step: the learner-side scoring pass over the same
     ragged histories (per-token log-probabilities, logits never written) and the truncated sampler in the
-    paper's evaluation setting (temperature 0.6, top-p 0.95) on the step's logits."""
+    paper's evaluation setting (temperature 0.6, top-p 0.95) on one step's logits."""
     import torch
     g = wl.geometry
     B = len(prompts)
@@ -162,42 +168,74 @@ def next_rows(sess, sb, wl, prompts, ids, logits, group_tokens):
     us_trunc = timed(lambda: sb.spiral_sample_truncated(logits, B, g.vocab, 0.6, 0, 0.95, 1, ids, steps, None, out_tok, None))
     nbytes = B * g.vocab * 4
     rep["sample_truncated"] = {"setting": "T=0.6, top-p 0.95", "us": us_trunc, "us_untruncated": us_plain,
-                               "logits_bytes": nbytes, "GBps": nbytes / us_trunc / 1e3,
-                               "note": "6 passes over the row (max, 4 radix digits of probability mass, draw); ALU/LDS-atomic bound"}
+                               "logits_bytes": nbytes, "GBps": nbytes / us_trunc / 1e3}
     log(f"[bench] sampler: untruncated {us_plain:.0f} us, T=0.6 top-p 0.95 {us_trunc:.0f} us")
     return rep
 
 
-def cpu_baseline(wl, prompts, weights_dev, n_steps=48):
-    """The oracle's KV-cached decoder (fp32 variant) on the host: one sequence of the batch (the
-    shortest prompt), prompt consumed untimed, n_steps decode steps timed."""
+def host_cpu():
+    """(model name, physical cores) of this machine, from /proc/cpuinfo."""
+    model, cores = "unknown", set()
+    try:
+        phys = core = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name") and model == "unknown":
+                model = line.split(":", 1)[1].strip()
+            elif line.startswith("physical id"):
+                phys = line.split(":", 1)[1].strip()
+            elif line.startswith("core id"):
+                core = line.split(":", 1)[1].strip()
+            elif not line.strip():
+                if phys is not None and core is not None:
+                    cores.add((phys, core))
+                phys = core = None
+    except OSError:
+        pass
+    return model, (len(cores) or (os.cpu_count() or 1))
+
+
+def cpu_baseline(wl, prompts, weights_dev, n_seqs=4, n_steps=16):
+    """The oracle's KV-cached decoder (its fp32 variant, to bound the sample) on the host: sequences 0..n_seqs-1
+    of the batch one after the other, each prompt consumed untimed, then n_steps greedy decode steps timed."""
     from oracle import decoder as od
     from paper_2506_24119_amd import inputs as si
     import torch
     g = wl.geometry
     t0 = time.time()
     w_host = si.weights_to_host_numpy(weights_dev)
-    b = int(np.argmin([len(p) for p in prompts]))
     dec = od.CachedDecoder(g, w_host, dtype=np.float32)
     log(f"[bench] oracle weights widened in {time.time() - t0:.1f}s")
-    t0 = time.time()
-    lg = dec.prefill(prompts[b])
-    log(f"[bench] oracle prefill of {len(prompts[b])} tokens: {time.time() - t0:.1f}s")
-    tok = int(np.argmax(lg))
-    t0 = time.time()
-    for _ in range(n_steps):
-        lg = dec.step(tok)
+    n_seqs = min(n_seqs, len(prompts))
+    timed_s, timed_tokens = 0.0, 0
+    for b in range(n_seqs):
+        dec.k = [np.zeros((0, g.n_kv_heads, g.head_dim), np.float32) for _ in dec.layers]       # a fresh, empty cache
+        dec.v = [np.zeros((0, g.n_kv_heads, g.head_dim), np.float32) for _ in dec.layers]
+        dec.n = 0
+        t0 = time.time()
+        lg = dec.prefill(prompts[b])
+        log(f"[bench] oracle sequence {b}: prefill of {len(prompts[b])} tokens {time.time() - t0:.1f}s")
         tok = int(np.argmax(lg))
-    dt = time.time() - t0
-    cores = torch.get_num_threads()
+        t0 = time.time()
+        for _ in range(n_steps):
+            lg = dec.step(tok)
+            tok = int(np.argmax(lg))
+        timed_s += time.time() - t0
+        timed_tokens += n_steps
+    threads = torch.get_num_threads()
     try:
         from threadpoolctl import threadpool_info
-        cores = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
     except Exception:
         pass
-    return {"value": n_steps / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"1 of {wl.batch} sequences (prompt {len(prompts[b])} tokens, consumed untimed), "
-                      f"{n_steps} KV-cached decode steps, numpy fp32"}
+    model, phys = host_cpu()
+    rate = timed_tokens / timed_s
+    return {"value": rate, "unit": "tokens/s", "cores": int(threads), "kind": "oracle", "cpu_model": model, "physical_cores": phys,
+            "sample": f"sequences 0..{n_seqs - 1} of {wl.batch} one after the other (prompts of "
+                      f"{[len(p) for p in prompts[:n_seqs]]} tokens consumed untimed), {n_steps} KV-cached decode steps each timed, "
+                      f"numpy fp32 on {threads} threads",
+            "extrapolated_full_batch_tokens_per_s": rate,
+            "extrapolation_note": "the oracle decodes one sequence at a time, so its rate for the whole batch is the same "
+                                  "tokens/s (the batch takes batch/n_seqs times as long), not a sum over sequences"}
 
 
 def main():
@@ -206,6 +244,11 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"])
+    ap.add_argument("--repeats", type=int, default=3)
+    ap.add_argument("--window", default="centered", choices=["centered", "start"],
+                    help="where K < run-length timed steps sit in the decode run")
+    ap.add_argument("--unfused", action="store_true", help="spiral_decode_step + spiral_sample instead of the fused step")
+    ap.add_argument("--tune", default=None, help="spiral_model_tune spec (launch decompositions; measurement only)")
     ap.add_argument("--prefill-group-tokens", type=int, default=16384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
@@ -233,10 +276,15 @@ def main():
 
     wl = si.WORKLOADS[args.workload]
     g = wl.geometry
-    K = args.steps if args.steps is not None else wl.decode_steps
+    run_len = wl.decode_steps
+    K = args.steps if args.steps is not None else run_len
     W = args.warmup
+    R = max(1, args.repeats)
     B = wl.batch
-    sess, prompts, lens0 = build_session(wl, W + K, args.prefill_group_tokens)
+    fused = (not args.unfused) and g.weight_dtype == 1 and g.d_model % 128 == 0 and g.vocab % 16 == 0
+    # the timed window [P, P + K) of the run; the W warm-up steps are the ones just before it
+    P = max(W, (run_len - K) // 2) if (args.window == "centered" and K < run_len) else W
+    sess, prompts, lens0 = build_session(wl, P + K, args.prefill_group_tokens, tune=args.tune)
     ids = np.arange(B, dtype=np.int32)
     seed = 1000 + wl.seed
 
@@ -248,48 +296,70 @@ def main():
     log(f"[bench] prefill of {int(lens0.sum())} tokens: {prefill_s:.2f}s")
     tokens = torch.empty(B, dtype=torch.int32, device=sess.device)
     sess.sample(logits, wl.temperature, seed, ids, np.zeros(B, dtype=np.int32), tokens)
-    tokens0 = tokens.clone()
 
-    # ---- warm-up, then the timed region
-    run_steps(sess, sb, ids, logits, tokens, 1, W, wl.temperature, seed)
+    # ---- untimed steps up to the warm-up point of the window; the state there is what every repeat starts from
+    run_steps(sess, ids, logits, tokens, 1, P - W, wl.temperature, seed, fused)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(sess, sb, ids, logits, tokens, 1 + W, K, wl.temperature, seed)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    lens_start = (lens0 + (P - W)).astype(np.int32)
+    tokens_start = tokens.clone()
+
+    def rewind():
+        sb.spiral_seq_truncate(sess.pool, ids, lens_start)
+        tokens.copy_(tokens_start)
+
+    times = []
+    for r in range(R):
+        rewind()
+        run_steps(sess, ids, logits, tokens, 1 + P - W, W, wl.temperature, seed, fused)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(sess, ids, logits, tokens, 1 + P, K, wl.temperature, seed, fused)
+        torch.cuda.synchronize()
+        times.append(time.perf_counter() - t0)
+        log(f"[bench] repeat {r}: {K} steps in {times[-1]:.3f}s -> {B * K / times[-1]:.0f} tokens/s")
+    dt = float(np.median(times))
     tok_per_s = B * K / dt
-    log(f"[bench] {K} steps in {dt:.3f}s -> {tok_per_s:.0f} tokens/s")
 
     total_bytes, attn_bytes = 0, 0
     for k in range(K):
-        tb, ab = algorithmic_bytes(g, lens0 + W + k + 1, B)
+        tb, ab = algorithmic_bytes(g, lens0 + P + k + 1, B, fused)
         total_bytes += tb
         attn_bytes += ab * g.n_layers
     step_gbps = total_bytes / dt / 1e9
 
-    # ---- dominant kernel: rewind to the start of the timed region and replay it with HIP events
+    # ---- what this GPU streams: a pure load kernel over a buffer the size of one attention launch's K/V
+    probe_bytes = int(min(max(attn_bytes // max(K * g.n_layers, 1), 64 << 20), sess.pool_mem.numel()) // 4096 * 4096)
+    stream_gbps = sb.spiral_probe_stream_read(sess.pool_mem, probe_bytes, iters=10)
+    log(f"[bench] streaming read of {probe_bytes / 1e6:.0f} MB: {stream_gbps:.0f} GB/s")
+
+    # ---- dominant kernel: replay the window with HIP events around every decode-attention launch
     roofline = {"bound": "hbm", "kernel": "attn_stream_kernel (paged decode attention, balanced page stream)", "achieved": None,
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": None, "traffic": None}
     if not args.no_kernel_timing:
-        sb.spiral_seq_truncate(sess.pool, ids, lens0)
-        tokens.copy_(tokens0)
-        run_steps(sess, sb, ids, logits, tokens, 1, W, wl.temperature, seed)
+        rewind()
+        run_steps(sess, ids, logits, tokens, 1 + P - W, W, wl.temperature, seed, fused)
         torch.cuda.synchronize()
         sb.spiral_profile_begin(sess.model, sb.KERNEL_CLASSES.index("attn_decode"), K * g.n_layers)
-        run_steps(sess, sb, ids, logits, tokens, 1 + W, K, wl.temperature, seed)
+        run_steps(sess, ids, logits, tokens, 1 + P, K, wl.temperature, seed, fused)
         ms, n = sb.spiral_profile_end(sess.model)
         assert n == K * g.n_layers, (n, K * g.n_layers)
         achieved = attn_bytes / (ms * 1e-3) / 1e9
-        # HBM bytes per launch from rocprofv3 PMC (profiles/attn_decode_c3_pmc_traffic.md): FETCH_SIZE x 2.00
-        # (calibrated on plain copies) + WRITE_SIZE x 1.00 = 1.032 x the algorithmic bytes
-        roofline.update({"traffic": PMC_TRAFFIC_OVER_ALGORITHMIC * attn_bytes / n,
-                         "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on C3, copy-calibrated: "
-                                           "1.032 x algorithmic bytes (profiles/attn_decode_c3_pmc_traffic.md)",
-                         "achieved": achieved, "frac": achieved / HBM_PEAK_GBPS,
-                         "avg_launch_us": 1e3 * ms / n, "launches": n,
-                         "algorithmic_bytes_per_launch": attn_bytes / n})
+        roofline.update({"achieved": achieved, "frac": achieved / HBM_PEAK_GBPS, "avg_launch_us": 1e3 * ms / n, "launches": n,
+                         "algorithmic_bytes_per_launch": attn_bytes / n,
+                         "frac_of_measured_stream": achieved / stream_gbps})
+        try:
+            tj = json.load(open(TRAFFIC_JSON))
+            roofline["traffic"] = tj["hbm_bytes_over_algorithmic_bytes"] * attn_bytes / n
+            roofline["traffic_source"] = {k: tj[k] for k in ("hbm_bytes_over_algorithmic_bytes", "measured_at_commit", "method", "file")}
+        except (OSError, KeyError, ValueError) as e:
+            roofline["traffic_source"] = f"unavailable: {e}"
         log(f"[bench] attention: {n} launches, avg {1e3 * ms / n:.1f} us, {achieved:.0f} GB/s")
+    # the quantity the target is stated on: algorithmic bytes of the whole step / step time
+    roofline.update({"step_achieved": step_gbps, "step_frac": step_gbps / HBM_PEAK_GBPS,
+                     "step_frac_of_measured_stream": step_gbps / stream_gbps, "measured_stream_GBps": stream_gbps,
+                     "step_algorithmic_GB": total_bytes / K / 1e9})
 
+    window = "whole run" if K >= run_len else f"steps [{P}, {P + K}) of the {run_len}-step run ({args.window} window)"
     out = {
         "metric": "generated tokens/sec on 1 MI355X (Qwen3-4B-shaped decode); % HBM roofline",
         "value": tok_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -298,8 +368,10 @@ def main():
                  if "f16 MFMA" in sb.spiral_version() else "bf16",
         "data": "synthetic",
         "config": {"workload": f"{wl.key}: {g.name}-shaped random init, batch {B}, prompts U[{wl.prompt_lo},{wl.prompt_hi}], "
-                               f"{K} decode steps, T={wl.temperature} seeded Gumbel-max sampling, 16-token pages",
-                   "context_tokens_start": int((lens0 + W).sum()), "context_tokens_end": int((lens0 + W + K).sum())},
+                               f"{run_len} decode steps, T={wl.temperature} seeded Gumbel-max sampling, 16-token pages; timed: {window}",
+                   "timed_window": [P, P + K], "run_steps": run_len, "repeats": R, "repeat_seconds": times,
+                   "step_call": "spiral_decode_sample_step" if fused else "spiral_decode_step + spiral_sample",
+                   "context_tokens_start": int((lens0 + P).sum()), "context_tokens_end": int((lens0 + P + K).sum())},
         "hbm_step": {"algorithmic_GB_per_step": total_bytes / K / 1e9, "achieved_GBps": step_gbps,
                      "frac_of_8TBps": step_gbps / HBM_PEAK_GBPS},
         "prefill_s": prefill_s,
@@ -307,7 +379,9 @@ def main():
     }
     out["prefill"] = prefill_report(g, prompts, prefill_s, score=False)
     if not args.no_extras and g.weight_dtype == 1 and g.d_model % 128 == 0:
+        sess.decode_step(ids, tokens, logits)          # one step's logits for the sampler timings
         out["next_rows"] = next_rows(sess, sb, wl, prompts, ids, logits, args.prefill_group_tokens)
+    out["saturated_activation_stores"] = sess.saturation_count()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, prompts, sess.weights)
     print(json.dumps(out), flush=True)

@@ -116,8 +116,7 @@ int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* s
 /* Measurement / test hook: overrides the launch decomposition the library would choose from the geometry.
  * spec is a comma-separated list of key=value items (unknown keys are ignored): "qkv=R:S", "o=R:S", "down=R:S"
  * (weight rows per workgroup : K splits of that projection), "gu=R", "lm=R", "chunk=P" (least pages per
- * attention workgroup), "stream=0|1" (decode attention as one balanced page stream, or one workgroup per chunk
- * of P pages), "wgs=N" (workgroups of the stream kernel), "frag=0|1" (use the repacked weights),
+ * decode-attention workgroup), "wgs=N" (workgroups of the decode attention), "frag=0|1" (use the repacked weights),
  * "fail_after=N" (error-path tests: the N-th
  * kernel launch of the layer stack from now on is not made and reports a launch failure).  Results stay within
  * the parity tolerance for every setting; the defaults are the measured best.  "frag" must be set before
@@ -285,6 +284,12 @@ enum spiral_kernel_class {
 };
 int spiral_profile_begin(spiral_model* m, int kernel_class, int max_launches);
 int spiral_profile_end(spiral_model* m, double* host_total_ms, int* host_n_launches);
+/* Yardstick for the memory-bound kernels: reads dev_buf (bytes >= 1 MiB, 16-byte aligned) `iters` times with a pure
+ * streaming-load kernel shaped like the decode step's weight and K/V streams (3 workgroups per compute unit, eight
+ * non-temporal 16-byte loads per lane in flight) and reports the mean milliseconds of one pass, measured with
+ * HIP events on `stream`.  Unlike the rest of the library this call waits for its own work.  A buffer much smaller
+ * than the last-level cache measures the cache, not HBM.  Errors: INVALID_ARG, HIP. */
+int spiral_probe_stream_read(const void* dev_buf, size_t bytes, int iters, double* host_ms_per_pass, void* stream);
 
 /* ---- role-conditioned advantage estimation (host only, float64) -------------------------------
  * Baselines b[game][role], role in {0,1}, start at 0 (Alg. 1, initialisation).  spiral_rae_update

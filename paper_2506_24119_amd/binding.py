@@ -30,7 +30,7 @@ EXPORTS = [
     "spiral_seq_reset", "spiral_seq_truncate", "spiral_profile_begin", "spiral_profile_end", "spiral_seq_len", "spiral_kv_free_pages", "spiral_prefill", "spiral_decode_step",
     "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free", "spiral_model_tune", "spiral_kv_pool_status_offset", "spiral_decode_sample_step",
-    "spiral_decode_step_static", "spiral_static_workspace_bytes",
+    "spiral_decode_step_static", "spiral_static_workspace_bytes", "spiral_probe_stream_read",
 ]
 
 
@@ -109,6 +109,8 @@ def load_library(path: Optional[str] = None):
     lib.spiral_decode_step_static.argtypes = [vp, vp, i32p, C.c_int, vp, f32p, vp]
     lib.spiral_static_workspace_bytes.restype = C.c_size_t
     lib.spiral_static_workspace_bytes.argtypes = []
+    lib.spiral_probe_stream_read.restype = C.c_int
+    lib.spiral_probe_stream_read.argtypes = [vp, C.c_size_t, C.c_int, C.POINTER(C.c_double), vp]
     lib.spiral_model_tune.restype = C.c_int
     lib.spiral_model_tune.argtypes = [vp, C.c_char_p]
     lib.spiral_kv_pool_status_offset.restype = C.c_longlong
@@ -289,6 +291,13 @@ def spiral_decode_step_static(model: int, pool: int, seq_ids, dev_in_tokens, dev
 
 def spiral_static_workspace_bytes() -> int:
     return load_library().spiral_static_workspace_bytes()
+
+
+def spiral_probe_stream_read(dev_buf, nbytes: int, iters: int = 5, stream=None) -> float:
+    """-> GB/s of a pure streaming read over the first nbytes of dev_buf"""
+    ms = C.c_double(0.0)
+    _check(load_library().spiral_probe_stream_read(_ptr(dev_buf), C.c_size_t(nbytes), iters, C.byref(ms), _stream_handle(stream)))
+    return nbytes / (ms.value * 1e-3) / 1e9
 
 
 def spiral_model_tune(model: int, spec: str):

@@ -11,13 +11,11 @@
 // head (padded to 16), so K and V are read once per group.  Prefill: the rows are 16 consecutive
 // positions of one query head, each with its own causal limit.
 //
-// Decode: one workgroup = one tile x a range of pages; its four waves take pages round-robin, each with
-// a private online softmax (running max m, sum l, unnormalised O), merged through LDS at the end.
+// Decode (attn_stream_kernel): the ordered stream of all (row, kv head, page) units of the batch is cut into equal
+// ranges, one per workgroup; inside a range the four waves take pages round-robin, each with a private online
+// softmax (running max m, sum l, unnormalised O), merged through LDS at the end of every (row, kv head) segment;
+// a second small kernel merges the partial (m, l, O) of a pair that spans workgroups.
 // Prefill (attn_prefill_kernel): one wave = one tile over all its pages, four heads per workgroup.
-// Decode has two decompositions with the same inner loop: attn_stream_kernel (the default) cuts the
-// ordered stream of all (row, kv head, page) units of the batch into equal ranges, one per workgroup;
-// attn_kernel splits every sequence into chunks of `chunk_pages` pages, one workgroup each.  Either
-// way a second small kernel merges the partial (m, l, O) of a (row, head).
 // Softmax is evaluated in base 2: scores are scaled by log2(e)/sqrt(hd) and v_exp_f32 is 2^x.
 #include "spiral_internal.h"
 
@@ -84,141 +82,66 @@ __device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, i
     for (int mp = 0; mp < HD / 32; ++mp) f.v[mp] = NT ? KVLOAD((const u32x4*)((real ? vp : kp) + mp * step + off)) : *(const u32x4*)((real ? vp : kp) + mp * step + off);
 }
 
-template <int HD, bool ACT32>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
-    constexpr int KS = HD / 32, MT = HD / 16, OSTRIDE = HD + 4;
-    __shared__ float s_o[4][16 * OSTRIDE];
-    __shared__ float s_m[4][16];
-    __shared__ float s_l[4][16];
-
-    // the wave index as a scalar, so that block-table look-ups are scalar loads (their own wait counter)
-    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int li = lane & 15, lg = lane >> 4;
-    const int G = a.n_q_heads / a.n_kv_heads;
-
-    int seq, kvh, p_begin, p_end, limit, n_valid_rows;
-    const uint16_t* qptr = nullptr;       // this lane's query row (row li of the tile) or null
-    int row0 = 0;
-    {
-        const int r = blockIdx.z, c = blockIdx.x;
-        kvh = blockIdx.y;
-        seq = a.row_seq[r];
-        const int pos = a.row_pos[r];
-        const int n_pages = pos / kPageTokens + 1;
-        p_begin = c * a.chunk_pages;
-        if (p_begin >= n_pages) return;
-        p_end = min(p_begin + a.chunk_pages, n_pages);
-        n_valid_rows = G;
-        row0 = r;
-        limit = pos;
-        if (li < G) qptr = a.q + ((size_t)r * a.n_q_heads + kvh * G + li) * HD;
+// Online-softmax state of one 16-row tile in one wave, and the update for one page of 16 tokens:
+// S^T = K q^T (scores of the page's tokens against the tile's rows), base-2 softmax statistics per row with the
+// accumulator rescaled only when some row's maximum moved, then O^T += V^T P^T.  `limit` is the last visible
+// position of this lane's row (li); tokens beyond it get zero weight.
+template <int HD>
+struct TileState {
+    u32x4 qf[HD / 32];        // query rows as the B operand: row = li, d = ks*32 + lg*8 .. +8
+    f32x4 acc[HD / 16];       // O^T: lane (li, lg) holds d = mt*16 + lg*4 .. +3 of row li
+    float m_run, l_run;       // running maximum (base-2 scaled scores) and sum of weights, per row, spread over lg
+    __device__ __forceinline__ void reset() {
+#pragma unroll
+        for (int mt = 0; mt < HD / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = kNegBig; l_run = 0.f;
     }
+};
 
-    // query rows as the B operand: row = li, d = ks*32 + lg*8 .. +8
-    u32x4 qf[KS];
+template <int HD>
+__device__ __forceinline__ void page_step(TileState<HD>& t, const PageFrag<HD>& f, int pi, int limit, float scale_log2e, int lg) {
+    constexpr int KS = HD / 32, MT = HD / 16;
+    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-        qf[ks] = qptr ? *(const u32x4*)(qptr + ks * 32 + lg * 8) : u32x4{0u, 0u, 0u, 0u};
-
-    f32x4 acc[MT];
+    for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], t.qf[ks], s);
+    const int t0 = pi * kPageTokens + lg * 4;
+    float sv[4] = {s.x * scale_log2e, s.y * scale_log2e, s.z * scale_log2e, s.w * scale_log2e};
+    bool ok[4];
+    float mx = kNegBig;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = kNegBig, l_run = 0.f;
-
-    const int32_t* bt = a.block_table + (size_t)seq * a.max_blocks;
-    const size_t page_elems = (size_t)a.n_kv_heads * (2 * kPageTokens * HD);
-    const size_t head_off = (size_t)kvh * (2 * kPageTokens * HD);
-
-    auto step = [&](const PageFrag<HD>& f, int pi) {
-        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int r = 0; r < 4; ++r) {
+        ok[r] = (t0 + r) <= limit;
+        mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(t.m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(t.m_run - m_new);
+    float p[4];
+    float ps = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            s = mma_qk(f.k[ks], qf[ks], s);
-        const int t0 = pi * kPageTokens + lg * 4;
-        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
-        bool ok[4];
-        float mx = kNegBig;
+    for (int r = 0; r < 4; ++r) {
+        p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
+        ps += p[r];
+    }
+    t.l_run = t.l_run * alpha + ps;
+    const float m_prev = t.m_run;
+    t.m_run = m_new;
+    u32x2 pb;
+    pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
+    pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
+    // the running maximum settles after a few pages: rescale O only when some row's maximum moved
+    if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            ok[r] = (t0 + r) <= limit;
-            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        float p[4];
-        float ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
-            ps += p[r];
-        }
-        l_run = l_run * alpha + ps;
-        const float m_prev = m_run;
-        m_run = m_new;
-        u32x2 pb;
-        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
-        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
-        // the running maximum settles after a few pages: rescale O only when some row's maximum moved
-        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
-            }
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-        {
-            const u32x4 vv = f.v[mt >> 1];
-            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
-            acc[mt] = mma_pv(vt, pb, acc[mt]);
-        }
-    };
-
-    // pages wave, wave+4, ... of [p_begin, p_end); the next page is in flight while one is consumed.
-    // The prefetch is unconditional (past the end it re-reads one valid 16-byte spot) so that the
-    // compiler's wait counts let it stay in flight during the arithmetic.
-    int pi = p_begin + wave;
-    if (pi < p_end) {
-        PageFrag<HD> cur, nxt;
-        load_page<HD>(cur, a.pages + (size_t)bt[pi] * page_elems + head_off, lane, true);
-        while (true) {
-            const int pn = pi + 4;
-            const bool more = pn < p_end;
-            load_page<HD>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, lane, more);
-            step(cur, pi);
-            if (!more) break;
-            cur = nxt;
-            pi = pn;
+        for (int mt = 0; mt < MT; ++mt) {
+            t.acc[mt].x *= alpha; t.acc[mt].y *= alpha; t.acc[mt].z *= alpha; t.acc[mt].w *= alpha;
         }
     }
-
-    // ---- merge the four waves
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (lg == 0) { s_m[wave][li] = m_run; s_l[wave][li] = l_run; }
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
-        const f32x4 o = acc[mt];
-        *(float4*)&s_o[wave][li * OSTRIDE + mt * 16 + lg * 4] = make_float4(o.x, o.y, o.z, o.w);
-    }
-    __syncthreads();
-
-    for (int e = threadIdx.x; e < 16 * HD; e += 256) {
-        const int j = e / HD, i = e % HD;
-        if (j >= n_valid_rows) continue;
-        const float M = fmaxf(fmaxf(s_m[0][j], s_m[1][j]), fmaxf(s_m[2][j], s_m[3][j]));
-        float L = 0.f, O = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            const float sc = __builtin_amdgcn_exp2f(s_m[w][j] - M);
-            L += s_l[w][j] * sc;
-            O += s_o[w][j * OSTRIDE + i] * sc;
-        }
-        float* dst = a.part + ((((size_t)row0 * a.n_kv_heads + kvh) * a.n_chunks + blockIdx.x) * G + j) * (HD + 2);
-        dst[i] = O;
-        if (i == 0) { dst[HD] = M; dst[HD + 1] = L; }
+        const u32x4 vv = f.v[mt >> 1];
+        const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
+        t.acc[mt] = mma_pv(vt, pb, t.acc[mt]);
     }
 }
 
@@ -247,69 +170,23 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
     const int limit = li < n_valid_rows ? pos0 + li : -1;
     const int p_end = (pos0 + n_valid_rows - 1) / kPageTokens + 1;
 
-    u32x4 qf[KS];
+    TileState<HD> t;
     {
         const uint16_t* qptr = a.q + ((size_t)(row0 + (li < n_valid_rows ? li : 0)) * a.n_q_heads + h) * HD + lg * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 v = *(const u32x4*)(qptr + ks * 32);
-            qf[ks] = li < n_valid_rows ? v : u32x4{0u, 0u, 0u, 0u};
+            t.qf[ks] = li < n_valid_rows ? v : u32x4{0u, 0u, 0u, 0u};
         }
     }
-    f32x4 acc[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = kNegBig, l_run = 0.f;
+    t.reset();
 
     const int32_t* bt = a.block_table + (size_t)seq * a.max_blocks;
     const size_t page_elems = (size_t)a.n_kv_heads * (2 * kPageTokens * HD);
     const size_t head_off = (size_t)kvh * (2 * kPageTokens * HD);
-
-    auto step = [&](const PageFrag<HD>& f, int pi) {
-        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], qf[ks], s);
-        const int t0 = pi * kPageTokens + lg * 4;
-        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
-        bool ok[4];
-        float mx = kNegBig;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            ok[r] = (t0 + r) <= limit;
-            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        float p[4];
-        float ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
-            ps += p[r];
-        }
-        l_run = l_run * alpha + ps;
-        const float m_prev = m_run;
-        m_run = m_new;
-        u32x2 pb;
-        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
-        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
-        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
-            }
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 vv = f.v[mt >> 1];
-            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
-            acc[mt] = mma_pv(vt, pb, acc[mt]);
-        }
-    };
-
     {
+        // the next page is in flight while one is consumed; the prefetch is unconditional (past the end it re-reads
+        // one valid 16-byte spot) so that the compiler's wait counts let it stay in flight during the arithmetic
         PageFrag<HD> cur, nxt;
         int pi = 0;
         load_page<HD, false>(cur, a.pages + (size_t)bt[0] * page_elems + head_off, lane, true);
@@ -317,7 +194,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
             const int pn = pi + 1;
             const bool more = pn < p_end;
             load_page<HD, false>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, lane, more);
-            step(cur, pi);
+            page_step<HD>(t, cur, pi, limit, a.scale_log2e, lg);
             if (!more) break;
             cur = nxt;
             pi = pn;
@@ -325,6 +202,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
     }
 
     // O^T[d][row]: lane (li, lg) holds d = mt * 16 + lg * 4 .. + 3 of row li; l is spread over the four lane groups
+    float l_run = t.l_run;
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     if (li < n_valid_rows) {
@@ -332,33 +210,12 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
         const size_t o_idx = ((size_t)(row0 + li) * a.n_q_heads + h) * HD + lg * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 0, acc[mt].x * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 1, acc[mt].y * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 2, acc[mt].z * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 3, acc[mt].w * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 0, t.acc[mt].x * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 1, t.acc[mt].y * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 2, t.acc[mt].z * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 3, t.acc[mt].w * inv);
         }
     }
-}
-
-// merge the per-chunk partial results of one (row, query head)
-template <int HD, bool ACT32>
-__global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
-    const int r = blockIdx.x, h = blockIdx.y, i = threadIdx.x;
-    const int G = a.n_q_heads / a.n_kv_heads;
-    const int kvh = h / G, j = h % G;
-    const int n_pages = a.row_pos[r] / kPageTokens + 1;
-    const int n_chunks = (n_pages + a.chunk_pages - 1) / a.chunk_pages;
-    const float* base = a.part + (((size_t)r * a.n_kv_heads + kvh) * a.n_chunks * G + j) * (HD + 2);
-    const size_t cstride = (size_t)G * (HD + 2);
-    float M = kNegBig;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, base[c * cstride + HD]);
-    float L = 0.f, O = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const float sc = __builtin_amdgcn_exp2f(base[c * cstride + HD] - M);
-        L += base[c * cstride + HD + 1] * sc;
-        O += base[c * cstride + i] * sc;
-    }
-    ActStore<ACT32>::put(a.out, ((size_t)r * a.n_q_heads + h) * HD + i, O / L);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -368,7 +225,7 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(AttnArgs a) {
 // page counts, so unit u of row r is u - row_page_start[r] * Hkv = kvh * pages(r) + page.  Workgroup
 // w owns units [w * U, (w + 1) * U): every workgroup streams the same number of pages whatever the
 // mix of sequence lengths, and a workgroup's range is cut into segments at (row, kv head)
-// boundaries.  Within a segment the four waves take pages round-robin as in attn_kernel; at the end
+// boundaries.  Within a segment the four waves take pages round-robin; at the end
 // of a segment they merge through LDS and write one partial (m, l, O) into slot
 // (row, kv head, w - first workgroup of that pair).  While a wave finishes a segment its first page of
 // the next segment is already in flight and the next query rows are loaded under the merge, so the
@@ -418,69 +275,18 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
     const size_t page_elems = (size_t)Hkv * (2 * kPageTokens * HD);
     constexpr int head_elems = 2 * kPageTokens * HD;
 
-    u32x4 qf[KS];
+    TileState<HD> t;
+    int limit;
     auto load_q = [&](const Seg& sg) {
         // rows >= G of the tile are padding: they read row 0's vector and are zeroed
         const uint16_t* qp = a.q + ((size_t)sg.r * a.n_q_heads + sg.kvh * G + (li < G ? li : 0)) * HD + lg * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 v = *(const u32x4*)(qp + ks * 32);
-            qf[ks] = li < G ? v : u32x4{0u, 0u, 0u, 0u};
+            t.qf[ks] = li < G ? v : u32x4{0u, 0u, 0u, 0u};
         }
     };
-
-    f32x4 acc[MT];
-    float m_run, l_run;
-    int limit;
-    auto reset = [&](const Seg& sg) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m_run = kNegBig; l_run = 0.f; limit = sg.pos;
-    };
-
-    auto step = [&](const PageFrag<HD>& f, int pi) {
-        f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], qf[ks], s);
-        const int t0 = pi * kPageTokens + lg * 4;
-        float sv[4] = {s.x * a.scale_log2e, s.y * a.scale_log2e, s.z * a.scale_log2e, s.w * a.scale_log2e};
-        bool ok[4];
-        float mx = kNegBig;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            ok[r] = (t0 + r) <= limit;
-            mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
-        }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        float p[4];
-        float ps = 0.f;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
-            ps += p[r];
-        }
-        l_run = l_run * alpha + ps;
-        const float m_prev = m_run;
-        m_run = m_new;
-        u32x2 pb;
-        pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
-        pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
-        if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                acc[mt].x *= alpha; acc[mt].y *= alpha; acc[mt].z *= alpha; acc[mt].w *= alpha;
-            }
-        }
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const u32x4 vv = f.v[mt >> 1];
-            const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
-            acc[mt] = mma_pv(vt, pb, acc[mt]);
-        }
-    };
+    auto reset = [&](const Seg& sg) { t.reset(); limit = sg.pos; };
 
     PageFrag<HD> cur_f, nxt_f;
     bool have = cur.p0 + wave < cur.p1;         // cur_f holds (or is being loaded with) this wave's first page of `cur`
@@ -522,7 +328,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
                 const int idx = more ? pn : (cross ? pn0 : nxt.p0);      // nxt.p0 is a valid entry (nxt = cur without a successor)
                 const int kv = more ? cur.kvh : nxt.kvh;
                 load_page<HD>(nxt_f, a.pages + (size_t)btp[idx] * page_elems + (size_t)kv * head_elems, lane, real);
-                step(cur_f, pi);
+                page_step<HD>(t, cur_f, pi, limit, a.scale_log2e, lg);
                 cur_f = nxt_f;
                 if (!more) break;
                 pi = pn;
@@ -532,12 +338,13 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
         }
 
         // ---- merge the four waves and write this segment's partial result
-        l_run += __shfl_xor(l_run, 16, 64);
-        l_run += __shfl_xor(l_run, 32, 64);
-        const float m_fin = m_run, l_fin = l_run;
+        float l_fin = t.l_run;
+        l_fin += __shfl_xor(l_fin, 16, 64);
+        l_fin += __shfl_xor(l_fin, 32, 64);
+        const float m_fin = t.m_run;
         f32x4 o_fin[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) o_fin[mt] = acc[mt];
+        for (int mt = 0; mt < MT; ++mt) o_fin[mt] = t.acc[mt];
         if (has_next) { load_q(nxt); reset(nxt); }     // the query rows of the next segment arrive under the merge
 
         __syncthreads();                               // the previous segment's merge has been read
@@ -635,38 +442,6 @@ hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hip
         case 32:  return act32 ? stream_combine_impl<32, true>(a, s) : stream_combine_impl<32, false>(a, s);
         case 64:  return act32 ? stream_combine_impl<64, true>(a, s) : stream_combine_impl<64, false>(a, s);
         case 128: return act32 ? stream_combine_impl<128, true>(a, s) : stream_combine_impl<128, false>(a, s);
-    }
-    return hipErrorInvalidValue;
-}
-
-template <int HD, bool ACT32>
-static hipError_t decode_impl(const AttnArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((attn_kernel<HD, ACT32>), dim3(a.n_chunks, a.n_kv_heads, a.n_rows), dim3(256), 0, s, a);
-    return hipGetLastError();
-}
-
-template <int HD, bool ACT32>
-static hipError_t combine_impl(const AttnArgs& a, hipStream_t s) {
-    hipLaunchKernelGGL((attn_combine_kernel<HD, ACT32>), dim3(a.n_rows, a.n_q_heads), dim3(HD), 0, s, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
-    if (a.n_rows <= 0 || a.n_chunks <= 0 || a.n_q_heads / a.n_kv_heads > kMaxGroup) return hipErrorInvalidValue;
-    switch (hd) {
-        case 32:  return act32 ? decode_impl<32, true>(a, s) : decode_impl<32, false>(a, s);
-        case 64:  return act32 ? decode_impl<64, true>(a, s) : decode_impl<64, false>(a, s);
-        case 128: return act32 ? decode_impl<128, true>(a, s) : decode_impl<128, false>(a, s);
-    }
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s) {
-    if (a.n_rows <= 0 || a.n_chunks <= 0) return hipErrorInvalidValue;
-    switch (hd) {
-        case 32:  return act32 ? combine_impl<32, true>(a, s) : combine_impl<32, false>(a, s);
-        case 64:  return act32 ? combine_impl<64, true>(a, s) : combine_impl<64, false>(a, s);
-        case 128: return act32 ? combine_impl<128, true>(a, s) : combine_impl<128, false>(a, s);
     }
     return hipErrorInvalidValue;
 }

@@ -464,6 +464,29 @@ hipError_t launch_sample(const float* logits, int B, int V, float temperature, c
     return hipSuccess;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Measurement: a pure streaming read with the access pattern of the decode step's once-read streams (every
+// wave keeps eight 16-byte loads per lane in flight, non-temporal), as the yardstick for "what this GPU streams".
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* p, size_t n16) {
+    size_t i = (size_t)blockIdx.x * 256 * 8 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256 * 8;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (; i + 256 * 7 < n16; i += stride) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + i + 256 * u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    asm volatile("" ::"v"(acc.x ^ acc.y ^ acc.z ^ acc.w));      // keeps the loads alive; nothing is written
+}
+
+hipError_t launch_stream_read(const void* p, size_t bytes, int workgroups, hipStream_t s) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(256), 0, s, (const u32x4*)p, bytes / 16);
+    return hipGetLastError();
+}
+
 // Second half of the fused LM head + sampler: the winner among the per-tile (score, index) pairs of a row.
 __global__ __launch_bounds__(256) void sample_pick_kernel(const float2* part, int n_tiles, int32_t* out) {
     __shared__ float s_v[4];

@@ -53,9 +53,8 @@ struct Tune {
     int bn_gu = 0;                 // 0: waves per workgroup chosen from the shape
     int bn_down = 0, s_down = 0;
     int bn_lm = 128;
-    int chunk_pages = 16;          // decode attention: pages per chunk (chunked kernel), least pages per workgroup (stream kernel)
-    int attn_stream = 1;           // 1: balanced page stream over the whole batch; 0: one workgroup per chunk
-    int attn_wgs = 0;              // workgroups of the stream kernel; 0 = 3 per compute unit (its occupancy)
+    int chunk_pages = 16;          // decode attention: least (row, kv head, page) units per workgroup
+    int attn_wgs = 0;              // workgroups of the decode attention; 0 = 3 per compute unit (its occupancy)
     int frag = 1;                  // 0: ignore spiral_model_repack (weights stay row-major; for A/B measurements)
     int fail_after = 0;            // test hook: the n-th timed launch from now reports a launch failure instead of running
 };
@@ -115,7 +114,6 @@ static void parse_tune(Tune& t, const char* e) {
                 else if (k == "down") { t.bn_down = a; if (n == 2) t.s_down = b; }
                 else if (k == "lm") { t.bn_lm = a; }
                 else if (k == "chunk") { t.chunk_pages = a; }
-                else if (k == "stream") { t.attn_stream = a; }
                 else if (k == "wgs") { t.attn_wgs = a; }
                 else if (k == "frag") { t.frag = a; }
                 else if (k == "fail_after") { t.fail_after = a; }
@@ -299,6 +297,29 @@ extern "C" int spiral_profile_end(spiral_model* m, double* host_total_ms, int* h
     *host_total_ms = total;
     *host_n_launches = n;
     drop_events(m->prof);
+    return SPIRAL_OK;
+}
+
+extern "C" int spiral_probe_stream_read(const void* dev_buf, size_t bytes, int iters, double* host_ms_per_pass, void* stream) {
+    if (!dev_buf || ((uintptr_t)dev_buf & 15) || bytes < (1u << 20) || iters < 1 || iters > 10000 || !host_ms_per_pass)
+        return fail(SPIRAL_ERR_INVALID_ARG, "probe_stream_read: needs a 16-byte aligned buffer of at least 1 MiB, 1 <= iters <= 10000 and an output");
+    hipStream_t s = (hipStream_t)stream;
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    hipError_t rc = hipEventCreate(&e1);
+    if (rc != hipSuccess) { (void)hipEventDestroy(e0); return fail(SPIRAL_ERR_HIP, "probe_stream_read: %s", hipGetErrorString(rc)); }
+    auto done = [&](hipError_t e) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return e; };
+    rc = launch_stream_read(dev_buf, bytes, 3 * cus, s);                       // untimed first pass
+    if (rc == hipSuccess) rc = hipEventRecord(e0, s);
+    for (int i = 0; i < iters && rc == hipSuccess; ++i) rc = launch_stream_read(dev_buf, bytes, 3 * cus, s);
+    if (rc == hipSuccess) rc = hipEventRecord(e1, s);
+    if (rc == hipSuccess) rc = hipEventSynchronize(e1);
+    float ms = 0.f;
+    if (rc == hipSuccess) rc = hipEventElapsedTime(&ms, e0, e1);
+    if (done(rc) != hipSuccess) return fail(SPIRAL_ERR_HIP, "probe_stream_read: %s", hipGetErrorString(rc));
+    *host_ms_per_pass = (double)ms / iters;
     return SPIRAL_OK;
 }
 
@@ -630,14 +651,11 @@ static int run_layers(StepCtx& c) {
         aa.n_rows = c.rows; aa.n_q_heads = cfg.n_q_heads; aa.n_kv_heads = cfg.n_kv_heads;
         aa.max_blocks = c.p->max_blocks; aa.chunk_pages = t.chunk_pages; aa.n_chunks = c.n_chunks;
         aa.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)hd));
-        if (c.decode && c.units_per_wg > 0) {
+        if (c.decode) {
             aa.row_page_start = c.w.page_start; aa.units_per_wg = c.units_per_wg; aa.total_units = c.total_units;
             aa.n_chunks = c.n_slots;
             HIP_TRY(timed(m, SPIRAL_K_ATTN_DECODE, c.s, [&] { return launch_attn_stream(aa, hd, act32, c.s); }));
             HIP_TRY(timed(m, SPIRAL_K_ATTN_COMBINE, c.s, [&] { return launch_attn_stream_combine(aa, hd, act32, c.s); }));
-        } else if (c.decode) {
-            HIP_TRY(timed(m, SPIRAL_K_ATTN_DECODE, c.s, [&] { return launch_attn_decode(aa, hd, act32, c.s); }));
-            HIP_TRY(timed(m, SPIRAL_K_ATTN_COMBINE, c.s, [&] { return launch_attn_combine(aa, hd, act32, c.s); }));
         } else {
             HIP_TRY(timed(m, SPIRAL_K_ATTN_PREFILL, c.s, [&] { return launch_attn_prefill(aa, hd, c.B, c.max_new, act32, c.s); }));
         }
@@ -856,7 +874,7 @@ static int decode_impl(spiral_model* m, spiral_kv_pool* p, const int32_t* host_s
                        w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps};
         HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
         StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
-        if (m->tune.attn_stream) {
+        {
             const int wgs = m->tune.attn_wgs > 0 ? m->tune.attn_wgs : 3 * m->n_cus;
             c.total_units = start[B] * m->cfg.n_kv_heads;
             c.units_per_wg = std::max(m->tune.chunk_pages, (c.total_units + wgs - 1) / wgs);

@@ -126,12 +126,11 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hip
 bool gemm_tile_usable(const GemmArgs& a);                                                  // fragment-ordered weights, K % 64 == 0, ...
 hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, hipStream_t s);
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s);   // K % 128 == 0, N % 16 == 0
-hipError_t launch_attn_decode(const AttnArgs& a, int hd, bool act32, hipStream_t s);
-hipError_t launch_attn_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_stream(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_prefill(const AttnArgs& a, int hd, int B, int max_new, bool act32, hipStream_t s);
 
+hipError_t launch_stream_read(const void* p, size_t bytes, int workgroups, hipStream_t s);
 hipError_t launch_sample_pick(const float2* part, int B, int n_tiles, int32_t* out, hipStream_t s);
 int gemm_sample_tile_cols(int M, int bn);     // LM-head columns per workgroup of the sampling epilogue
 hipError_t launch_sample(const float* logits, int B, int V, float temperature, const uint64_t* host_keys,

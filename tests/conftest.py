@@ -26,3 +26,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def progress(capfd):
+    """say(msg): prints past pytest's capture, so that a test whose CPU oracle runs for minutes shows it is alive."""
+    def say(msg):
+        with capfd.disabled():
+            print(msg, flush=True)
+    return say

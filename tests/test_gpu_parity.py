@@ -171,13 +171,11 @@ def test_long_context_spans_several_attention_chunks(sb):
     sess.close()
 
 
-@pytest.mark.parametrize("tune", ["stream=0", "stream=0,chunk=1", "stream=1,chunk=1,wgs=7", "stream=1,chunk=2,wgs=100000",
-                                  "stream=1,chunk=64,wgs=3"])
+@pytest.mark.parametrize("tune", ["chunk=1,wgs=7", "chunk=2,wgs=100000", "chunk=64,wgs=3", "chunk=1,wgs=1"])
 @pytest.mark.parametrize("name", ["g4-qknorm", "g7-bias"])
 def test_decode_attention_launch_shapes(sb, name, tune):
-    """The decode attention in every decomposition the library can choose: one workgroup per chunk of
-    pages, and the balanced page stream with workgroup ranges that cut (row, kv head) pairs at
-    arbitrary pages, hold many pairs, or hold one page each (spiral_model_tune selects them)."""
+    """The decode attention's page stream with workgroup ranges that cut (row, kv head) pairs at arbitrary
+    pages, hold many pairs, hold one page each, or are a single workgroup (spiral_model_tune selects them)."""
     g = SMALL[name]
     w = si.make_weights(g, seed=23)
     B, steps = 5, 18
