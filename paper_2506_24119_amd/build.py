@@ -1,9 +1,17 @@
 """Builds libspiral.so (HIP kernels + C ABI) for gfx950, in-tree.
 
-    python -m paper_2506_24119_amd.build [--act bf16|f16]
+    python -m paper_2506_24119_amd.build [--asan] [--out PATH]
 
 hipcc cross-compiles without a GPU.  The packed-fp32 target feature is switched
 off for every device compile.
+
+--asan builds libspiral_asan.so with AddressSanitizer and UndefinedBehaviorSanitizer on the
+HOST code only (argument checks, page bookkeeping, workspace carving, RAE; device code is
+compiled as usual), for running the host-only tests under the sanitizers on a CPU machine:
+
+    LD_PRELOAD="$LD_PRELOAD:$(python -m paper_2506_24119_amd.build --asan-runtime)" \
+    ASAN_OPTIONS=verify_asan_link_order=0:detect_leaks=0 SPIRAL_LIB=paper_2506_24119_amd/libspiral_asan.so \
+        python -m pytest tests/test_abi_host.py -q
 """
 from __future__ import annotations
 
@@ -20,11 +28,20 @@ SOURCES = ["spiral_api.hip", "kernels_misc.hip", "kernels_gemm.hip", "kernels_ge
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
-def _flags(act_f16: bool):
+ASAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+              "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def _flags(asan: bool = False):
     return ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            f"-DSPIRAL_ACT_F16={1 if act_f16 else 0}",
-            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+            "-I", os.path.join(ROOT, "include"), "-I", CSRC] + (ASAN_FLAGS if asan else [])
+
+
+def asan_runtime() -> str:
+    """Path of the shared AddressSanitizer runtime that matches hipcc's clang."""
+    r = subprocess.run([HIPCC, "-print-file-name=libclang_rt.asan-x86_64.so"], stdout=subprocess.PIPE, text=True)
+    return os.path.realpath(r.stdout.strip())
 
 
 def _compile(args):
@@ -35,10 +52,10 @@ def _compile(args):
     return src, r.returncode, out
 
 
-def build(act_f16: bool = True, lib: str = LIB, verbose: bool = True) -> str:
-    objdir = os.path.join(HERE, "_build", "f16" if act_f16 else "bf16")
+def build(lib: str = LIB, verbose: bool = True, asan: bool = False) -> str:
+    objdir = os.path.join(HERE, "_build", "asan" if asan else "f16")
     os.makedirs(objdir, exist_ok=True)
-    flags = _flags(act_f16)
+    flags = _flags(asan)
     jobs = [(s, os.path.join(objdir, s.rsplit(".", 1)[0] + ".o"), flags) for s in SOURCES]
     with ThreadPoolExecutor(max_workers=min(len(jobs), 8)) as ex:
         results = list(ex.map(_compile, jobs))
@@ -48,6 +65,8 @@ def build(act_f16: bool = True, lib: str = LIB, verbose: bool = True) -> str:
         if rc != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{out}")
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + [j[1] for j in jobs]
+    if asan:
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan", "-fno-gpu-sanitize"]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stdout)
@@ -57,10 +76,11 @@ def build(act_f16: bool = True, lib: str = LIB, verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    act = "f16"
-    if "--act" in sys.argv:
-        act = sys.argv[sys.argv.index("--act") + 1]
-    out = LIB
+    if "--asan-runtime" in sys.argv:
+        print(asan_runtime())
+        sys.exit(0)
+    asan = "--asan" in sys.argv
+    out = os.path.join(HERE, "libspiral_asan.so") if asan else LIB
     if "--out" in sys.argv:
         out = sys.argv[sys.argv.index("--out") + 1]
-    build(act_f16=(act == "f16"), lib=out)
+    build(lib=out, asan=asan)

@@ -46,18 +46,10 @@ constexpr float kNegBig = -1.0e30f;
 // q, the cached K/V and the probabilities share the 16-bit activation format (IEEE half by default:
 // with bf16's 8 significant bits the attention output alone carries ~0.4 % error per layer)
 __device__ __forceinline__ f32x4 mma_qk(const u32x4& k, const u32x4& q, const f32x4& c) {
-#if SPIRAL_ACT_F16
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, k), __builtin_bit_cast(f16x8, q), c, 0, 0, 0);
-#else
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k), __builtin_bit_cast(bf16x8, q), c, 0, 0, 0);
-#endif
 }
 __device__ __forceinline__ f32x4 mma_pv(const u32x2& v, const u32x2& p, const f32x4& c) {
-#if SPIRAL_ACT_F16
     return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, v), __builtin_bit_cast(f16x4, p), c, 0, 0, 0);
-#else
-    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, v), __builtin_bit_cast(s16x4, p), c, 0, 0, 0);
-#endif
 }
 
 // One (page, kv head) holds K then V, each 16 tokens x HD elements, stored in the order the MFMA
@@ -80,69 +72,6 @@ __device__ __forceinline__ void load_page(PageFrag<HD>& f, const uint16_t* kp, i
     for (int ks = 0; ks < HD / 32; ++ks) f.k[ks] = NT ? KVLOAD((const u32x4*)(kp + ks * step + off)) : *(const u32x4*)(kp + ks * step + off);
 #pragma unroll
     for (int mp = 0; mp < HD / 32; ++mp) f.v[mp] = NT ? KVLOAD((const u32x4*)((real ? vp : kp) + mp * step + off)) : *(const u32x4*)((real ? vp : kp) + mp * step + off);
-}
-
-// Online-softmax state of one 16-row tile in one wave, and the update for one page of 16 tokens:
-// S^T = K q^T (scores of the page's tokens against the tile's rows), base-2 softmax statistics per row with the
-// accumulator rescaled only when some row's maximum moved, then O^T += V^T P^T.  `limit` is the last visible
-// position of this lane's row (li); tokens beyond it get zero weight.
-template <int HD>
-struct TileState {
-    u32x4 qf[HD / 32];        // query rows as the B operand: row = li, d = ks*32 + lg*8 .. +8
-    f32x4 acc[HD / 16];       // O^T: lane (li, lg) holds d = mt*16 + lg*4 .. +3 of row li
-    float m_run, l_run;       // running maximum (base-2 scaled scores) and sum of weights, per row, spread over lg
-    __device__ __forceinline__ void reset() {
-#pragma unroll
-        for (int mt = 0; mt < HD / 16; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m_run = kNegBig; l_run = 0.f;
-    }
-};
-
-template <int HD>
-__device__ __forceinline__ void page_step(TileState<HD>& t, const PageFrag<HD>& f, int pi, int limit, float scale_log2e, int lg) {
-    constexpr int KS = HD / 32, MT = HD / 16;
-    f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s = mma_qk(f.k[ks], t.qf[ks], s);
-    const int t0 = pi * kPageTokens + lg * 4;
-    float sv[4] = {s.x * scale_log2e, s.y * scale_log2e, s.z * scale_log2e, s.w * scale_log2e};
-    bool ok[4];
-    float mx = kNegBig;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        ok[r] = (t0 + r) <= limit;
-        mx = ok[r] ? fmaxf(mx, sv[r]) : mx;
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(t.m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(t.m_run - m_new);
-    float p[4];
-    float ps = 0.f;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        p[r] = ok[r] ? __builtin_amdgcn_exp2f(sv[r] - m_new) : 0.f;
-        ps += p[r];
-    }
-    t.l_run = t.l_run * alpha + ps;
-    const float m_prev = t.m_run;
-    t.m_run = m_new;
-    u32x2 pb;
-    pb.x = (uint32_t)f32_to_act16(p[0]) | ((uint32_t)f32_to_act16(p[1]) << 16);
-    pb.y = (uint32_t)f32_to_act16(p[2]) | ((uint32_t)f32_to_act16(p[3]) << 16);
-    // the running maximum settles after a few pages: rescale O only when some row's maximum moved
-    if (__builtin_amdgcn_ballot_w64(m_new != m_prev) != 0) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            t.acc[mt].x *= alpha; t.acc[mt].y *= alpha; t.acc[mt].z *= alpha; t.acc[mt].w *= alpha;
-        }
-    }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const u32x4 vv = f.v[mt >> 1];
-        const u32x2 vt = (mt & 1) ? u32x2{vv.z, vv.w} : u32x2{vv.x, vv.y};
-        t.acc[mt] = mma_pv(vt, pb, t.acc[mt]);
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -170,20 +99,26 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
     const int limit = li < n_valid_rows ? pos0 + li : -1;
     const int p_end = (pos0 + n_valid_rows - 1) / kPageTokens + 1;
 
-    TileState<HD> t;
+    u32x4 qf[KS];
     {
         const uint16_t* qptr = a.q + ((size_t)(row0 + (li < n_valid_rows ? li : 0)) * a.n_q_heads + h) * HD + lg * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 v = *(const u32x4*)(qptr + ks * 32);
-            t.qf[ks] = li < n_valid_rows ? v : u32x4{0u, 0u, 0u, 0u};
+            qf[ks] = li < n_valid_rows ? v : u32x4{0u, 0u, 0u, 0u};
         }
     }
-    t.reset();
+    f32x4 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = kNegBig, l_run = 0.f;
 
     const int32_t* bt = a.block_table + (size_t)seq * a.max_blocks;
     const size_t page_elems = (size_t)a.n_kv_heads * (2 * kPageTokens * HD);
     const size_t head_off = (size_t)kvh * (2 * kPageTokens * HD);
+    auto step = [&](const PageFrag<HD>& f, int pi) {
+#include "attn_page_step.inc"
+    };
     {
         // the next page is in flight while one is consumed; the prefetch is unconditional (past the end it re-reads
         // one valid 16-byte spot) so that the compiler's wait counts let it stay in flight during the arithmetic
@@ -194,7 +129,7 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
             const int pn = pi + 1;
             const bool more = pn < p_end;
             load_page<HD, false>(nxt, a.pages + (size_t)bt[more ? pn : pi] * page_elems + head_off, lane, more);
-            page_step<HD>(t, cur, pi, limit, a.scale_log2e, lg);
+            step(cur, pi);
             if (!more) break;
             cur = nxt;
             pi = pn;
@@ -202,7 +137,6 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
     }
 
     // O^T[d][row]: lane (li, lg) holds d = mt * 16 + lg * 4 .. + 3 of row li; l is spread over the four lane groups
-    float l_run = t.l_run;
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
     if (li < n_valid_rows) {
@@ -210,10 +144,10 @@ __global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
         const size_t o_idx = ((size_t)(row0 + li) * a.n_q_heads + h) * HD + lg * 4;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 0, t.acc[mt].x * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 1, t.acc[mt].y * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 2, t.acc[mt].z * inv);
-            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 3, t.acc[mt].w * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 0, acc[mt].x * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 1, acc[mt].y * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 2, acc[mt].z * inv);
+            ActStore<ACT32>::put(a.out, o_idx + mt * 16 + 3, acc[mt].w * inv);
         }
     }
 }
@@ -275,7 +209,9 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
     const size_t page_elems = (size_t)Hkv * (2 * kPageTokens * HD);
     constexpr int head_elems = 2 * kPageTokens * HD;
 
-    TileState<HD> t;
+    u32x4 qf[KS];
+    f32x4 acc[MT];
+    float m_run, l_run;
     int limit;
     auto load_q = [&](const Seg& sg) {
         // rows >= G of the tile are padding: they read row 0's vector and are zeroed
@@ -283,10 +219,18 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const u32x4 v = *(const u32x4*)(qp + ks * 32);
-            t.qf[ks] = li < G ? v : u32x4{0u, 0u, 0u, 0u};
+            qf[ks] = li < G ? v : u32x4{0u, 0u, 0u, 0u};
         }
     };
-    auto reset = [&](const Seg& sg) { t.reset(); limit = sg.pos; };
+    auto reset = [&](const Seg& sg) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m_run = kNegBig; l_run = 0.f; limit = sg.pos;
+    };
+    auto step = [&](const PageFrag<HD>& f, int pi) {
+#include "attn_page_step.inc"
+    };
+
 
     PageFrag<HD> cur_f, nxt_f;
     bool have = cur.p0 + wave < cur.p1;         // cur_f holds (or is being loaded with) this wave's first page of `cur`
@@ -328,7 +272,7 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
                 const int idx = more ? pn : (cross ? pn0 : nxt.p0);      // nxt.p0 is a valid entry (nxt = cur without a successor)
                 const int kv = more ? cur.kvh : nxt.kvh;
                 load_page<HD>(nxt_f, a.pages + (size_t)btp[idx] * page_elems + (size_t)kv * head_elems, lane, real);
-                page_step<HD>(t, cur_f, pi, limit, a.scale_log2e, lg);
+                step(cur_f, pi);
                 cur_f = nxt_f;
                 if (!more) break;
                 pi = pn;
@@ -338,13 +282,12 @@ __global__ __launch_bounds__(256) void attn_stream_kernel(AttnArgs a) {
         }
 
         // ---- merge the four waves and write this segment's partial result
-        float l_fin = t.l_run;
-        l_fin += __shfl_xor(l_fin, 16, 64);
-        l_fin += __shfl_xor(l_fin, 32, 64);
-        const float m_fin = t.m_run;
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        const float m_fin = m_run, l_fin = l_run;
         f32x4 o_fin[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) o_fin[mt] = t.acc[mt];
+        for (int mt = 0; mt < MT; ++mt) o_fin[mt] = acc[mt];
         if (has_next) { load_q(nxt); reset(nxt); }     // the query rows of the next segment arrive under the merge
 
         __syncthreads();                               // the previous segment's merge has been read

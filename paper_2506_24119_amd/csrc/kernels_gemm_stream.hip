@@ -36,15 +36,9 @@ namespace spiral {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-#if SPIRAL_ACT_F16
 __device__ __forceinline__ f32x16 mma32(const u32x4& w, const u32x4& a, const f32x16& c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, a), c, 0, 0, 0);
 }
-#else
-__device__ __forceinline__ f32x16 mma32(const u32x4& w, const u32x4& a, const f32x16& c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0, 0, 0);
-}
-#endif
 
 template <int M32>
 struct Stage {

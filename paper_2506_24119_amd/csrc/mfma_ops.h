@@ -18,7 +18,6 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
-#if SPIRAL_ACT_F16
 // convert a weight fragment once, then reuse it for every batch tile
 __device__ __forceinline__ u32x4 prep_w(const u32x4& w) {
     u32x4 wh;
@@ -29,12 +28,6 @@ __device__ __forceinline__ u32x4 prep_w(const u32x4& w) {
 __device__ __forceinline__ f32x4 mma_prepped(const u32x4& w, const u32x4& a, const f32x4& c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, a), c, 0, 0, 0);
 }
-#else
-__device__ __forceinline__ u32x4 prep_w(const u32x4& w) { return w; }
-__device__ __forceinline__ f32x4 mma_prepped(const u32x4& w, const u32x4& a, const f32x4& c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, a), c, 0, 0, 0);
-}
-#endif
 
 __device__ __forceinline__ float silu_f(float z) { return z / (1.0f + __expf(-z)); }
 

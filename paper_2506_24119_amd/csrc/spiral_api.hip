@@ -36,11 +36,7 @@ static int fail(int code, const char* fmt, ...) {
 extern "C" const char* spiral_last_error(void) { return g_err; }
 int spiral_set_error(int code, const char* text) { return fail(code, "%s", text); }
 extern "C" const char* spiral_version(void) {
-#if SPIRAL_ACT_F16
     return "spiral-mi355x 0.1 (gfx950; bf16 weights, f16 activations/KV cache, f16 MFMA, f32 accumulate)";
-#else
-    return "spiral-mi355x 0.1 (gfx950; bf16 weights, bf16 activations/KV cache, bf16 MFMA, f32 accumulate)";
-#endif
 }
 
 // ---------------------------------------------------------------------------------------------

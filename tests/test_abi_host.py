@@ -169,3 +169,33 @@ def test_repack_plan_and_buffer_checks(lib):
         assert lib.spiral_model_repack_bytes(m) == 0
     finally:
         sb.spiral_model_free(m)
+
+
+def test_step_variants_and_hooks_validate_arguments_without_a_gpu(lib):
+    """The fused decode + sample step, the static-workspace step, the tuning call and the streaming probe refuse bad
+    arguments before any GPU call."""
+    def code(rc):
+        with pytest.raises(sb.SpiralError) as e:
+            sb._check(rc)
+        return e.value.code
+
+    fake = ctypes.c_void_p(0x10000)
+    assert code(lib.spiral_decode_sample_step(None, None, None, 1, fake, fake, 1 << 20, 1.0, 0, None, fake, None)) == sb.SPIRAL_ERR_NOT_LOADED
+    assert code(lib.spiral_decode_step_static(None, None, None, 1, fake, fake, None)) == sb.SPIRAL_ERR_NOT_LOADED
+    assert lib.spiral_static_workspace_bytes() == 16 << 20
+    assert code(lib.spiral_model_tune(None, b"chunk=4")) == sb.SPIRAL_ERR_NOT_LOADED
+    assert code(int(lib.spiral_kv_pool_status_offset(None))) == sb.SPIRAL_ERR_NOT_LOADED
+    ms = ctypes.c_double(0.0)
+    assert code(lib.spiral_probe_stream_read(None, 1 << 24, 1, ctypes.byref(ms), None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_probe_stream_read(fake, 1 << 10, 1, ctypes.byref(ms), None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_probe_stream_read(fake, 1 << 24, 0, ctypes.byref(ms), None)) == sb.SPIRAL_ERR_INVALID_ARG
+    g = si.ModelGeometry("tn", 1, 128, 4, 2, 32, 512, 1024, 1e4)
+    m = sb.spiral_model_load(sb.make_config(g), [0x100000 + 0x1000 * i for i in range(3 + sb.SPIRAL_LAYER_SLOTS)])
+    try:
+        sb.spiral_model_tune(m, "chunk=4,wgs=12,qkv=64:3,unknown=7,fail_after=0")      # unknown keys are ignored
+        assert code(lib.spiral_model_tune(m, None)) == sb.SPIRAL_ERR_INVALID_ARG
+        # pools of another model / null pools are refused by both step variants
+        assert code(lib.spiral_decode_step_static(m, None, None, 1, fake, fake, None)) == sb.SPIRAL_ERR_NOT_LOADED
+        assert code(lib.spiral_decode_sample_step(m, None, None, 1, fake, fake, 1 << 20, 1.0, 0, None, fake, None)) == sb.SPIRAL_ERR_NOT_LOADED
+    finally:
+        sb.spiral_model_free(m)
