@@ -264,6 +264,18 @@ int spiral_sample_truncated(const float* dev_logits, int B, int V, float tempera
                             uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
                             const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
                             void* stream);
+/* The same thresholds and the same draw (bit for bit) for long rows, in three sweeps of the logits instead of up to
+ * nine and by several workgroups per row: dev_workspace (device memory, 256-byte aligned, contents undefined before and
+ * after; calls that share it must be ordered on one stream) holds spiral_sample_truncated_workspace_bytes(B, V) bytes
+ * (0 for an invalid B or V).  Rows shorter than 16384 entries, a call that cuts nothing, and single rows whose
+ * scores are so crowded around the cut that more than 8192 of them fall within 1/128 of each other go through the
+ * kernel of spiral_sample_truncated.  Errors: as spiral_sample_truncated; INVALID_ARG for a null, misaligned or
+ * too small workspace. */
+size_t spiral_sample_truncated_workspace_bytes(int B, int V);
+int spiral_sample_truncated_ws(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                               uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                               const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                               void* dev_workspace, size_t workspace_bytes, void* stream);
 
 /* ---- measurement hooks (for benchmarks; not part of the method) --------------------------------
  * Between spiral_profile_begin and spiral_profile_end every launch of the chosen kernel class made

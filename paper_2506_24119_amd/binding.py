@@ -31,6 +31,7 @@ EXPORTS = [
     "spiral_sample", "spiral_sample_truncated", "spiral_score", "spiral_policy_objective", "spiral_rae_create", "spiral_rae_update", "spiral_rae_get", "spiral_rae_set",
     "spiral_rae_free", "spiral_model_tune", "spiral_kv_pool_status_offset", "spiral_decode_sample_step",
     "spiral_decode_step_static", "spiral_static_workspace_bytes", "spiral_probe_stream_read",
+    "spiral_sample_truncated_ws", "spiral_sample_truncated_workspace_bytes",
 ]
 
 
@@ -124,6 +125,11 @@ def load_library(path: Optional[str] = None):
     lib.spiral_sample_truncated.restype = C.c_int
     lib.spiral_sample_truncated.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp,
                                             vp, vp]
+    lib.spiral_sample_truncated_workspace_bytes.restype = C.c_size_t
+    lib.spiral_sample_truncated_workspace_bytes.argtypes = [C.c_int, C.c_int]
+    lib.spiral_sample_truncated_ws.restype = C.c_int
+    lib.spiral_sample_truncated_ws.argtypes = [f32p, C.c_int, C.c_int, C.c_float, C.c_int, C.c_float, C.c_uint64, i32p, i32p, vp, vp,
+                                               vp, vp, C.c_size_t, vp]
     lib.spiral_rae_create.restype = C.c_int
     lib.spiral_rae_create.argtypes = [C.c_int, C.c_double, C.POINTER(vp)]
     lib.spiral_rae_update.restype = C.c_int
@@ -338,6 +344,21 @@ def spiral_sample_truncated(dev_logits, B: int, V: int, temperature: float, top_
     _check(load_library().spiral_sample_truncated(_ptr(dev_logits), B, V, C.c_float(temperature), int(top_k), C.c_float(top_p),
                                                   C.c_uint64(seed), _ip(ids), _ip(st), _ptr(dev_noise), _ptr(dev_out_tokens),
                                                   _ptr(dev_threshold_out), _stream_handle(stream)))
+
+
+def spiral_sample_truncated_workspace_bytes(B: int, V: int) -> int:
+    return int(load_library().spiral_sample_truncated_workspace_bytes(B, V))
+
+
+def spiral_sample_truncated_ws(dev_logits, B: int, V: int, temperature: float, top_k: int, top_p: float, seed: int, seq_ids,
+                               steps, dev_noise, dev_out_tokens, dev_threshold_out, dev_workspace, workspace_bytes: int,
+                               stream=None):
+    ids = None if seq_ids is None else _i32(seq_ids)
+    st = None if steps is None else _i32(steps)
+    _check(load_library().spiral_sample_truncated_ws(_ptr(dev_logits), B, V, C.c_float(temperature), int(top_k), C.c_float(top_p),
+                                                     C.c_uint64(seed), _ip(ids), _ip(st), _ptr(dev_noise), _ptr(dev_out_tokens),
+                                                     _ptr(dev_threshold_out), _ptr(dev_workspace), C.c_size_t(workspace_bytes),
+                                                     _stream_handle(stream)))
 
 
 # ------------------------------------------------------------------------- RAE (host only)

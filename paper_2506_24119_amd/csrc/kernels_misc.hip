@@ -420,18 +420,23 @@ __global__ __launch_bounds__(1024) void sample_kernel(const float* logits, int V
     const uint64_t key = keys.key[row];
     float bv = -INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int v = threadIdx.x; v < V; v += 1024) {
-        float sc = lr[v];
-        if (mode != 0) {
-            float g;
-            if (mode == 2) {
-                g = nr[v];
-            } else {
-                g = gumbel_noise(key, v);
+    // eight loads in flight per thread (past the end they re-read the last entry: a branch around a load makes
+    // every load wait)
+    for (int base = threadIdx.x; base < V; base += 1024 * 8) {
+        float l[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) l[u] = lr[min(base + u * 1024, V - 1)];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int v = base + u * 1024;
+            if (v >= V) continue;
+            float sc = l[u];
+            if (mode != 0) {
+                const float g = mode == 2 ? nr[v] : gumbel_noise(key, v);
+                sc = sc / temperature + g;      // IEEE division, as the definition states it
             }
-            sc = sc / temperature + g;      // IEEE division, as the definition states it
+            if (better(sc, v, bv, bi)) { bv = sc; bi = v; }
         }
-        if (better(sc, v, bv, bi)) { bv = sc; bi = v; }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {

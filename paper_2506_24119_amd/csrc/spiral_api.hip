@@ -945,13 +945,19 @@ extern "C" int spiral_sample(const float* dev_logits, int B, int V, float temper
     return SPIRAL_OK;
 }
 
-extern "C" int spiral_sample_truncated(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
-                                       uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
-                                       const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
-                                       void* stream) {
+static int sample_truncated_impl(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                                 uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                                 const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                                 void* dev_workspace, size_t workspace_bytes, bool with_workspace, void* stream) {
     if (!(top_p > 0.f) || !(top_p <= 1.f)) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: top_p must be in (0, 1] (1 disables)");
     if (!(temperature >= 0.f) || !std::isfinite(temperature)) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: temperature must be finite and >= 0");
     if (temperature == 0.f && dev_threshold_out) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: greedy decoding has no threshold to report");
+    if (with_workspace) {
+        if (B < 1 || B > SPIRAL_MAX_BATCH || V < 1) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: bad B=%d or V=%d", B, V);
+        if (!dev_workspace || ((uintptr_t)dev_workspace & 255)) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: workspace is null or not 256-byte aligned");
+        const size_t need = sample_truncated_workspace_bytes(B, V);
+        if (workspace_bytes < need) return fail(SPIRAL_ERR_INVALID_ARG, "sample_truncated: workspace of %zu bytes, %zu needed", workspace_bytes, need);
+    }
     const bool cut = temperature > 0.f && ((top_k > 0 && top_k < V) || top_p < 1.f);
     if (!cut && !dev_threshold_out)      // nothing is truncated: the plain sampler is the same draw
         return spiral_sample(dev_logits, B, V, temperature, seed, host_seq_ids, host_steps, dev_noise, dev_out_tokens, stream);
@@ -965,7 +971,33 @@ extern "C" int spiral_sample_truncated(const float* dev_logits, int B, int V, fl
             keys[i] = row_key(seed, host_seq_ids[i], host_steps[i]);
         }
     }
-    HIP_TRY(launch_sample_truncated(dev_logits, B, V, temperature, top_k, top_p < 1.f ? top_p : 1.f, keys.data(), dev_noise,
-                                    dev_out_tokens, dev_threshold_out, (hipStream_t)stream));
+    // short rows leave nothing to share between workgroups; without a cut the single kernel needs two sweeps only
+    if (with_workspace && cut && V >= 16384)
+        HIP_TRY(launch_sample_truncated_ws(dev_logits, B, V, temperature, top_k, top_p < 1.f ? top_p : 1.f, keys.data(), dev_noise,
+                                           dev_out_tokens, dev_threshold_out, dev_workspace, (hipStream_t)stream));
+    else
+        HIP_TRY(launch_sample_truncated(dev_logits, B, V, temperature, top_k, top_p < 1.f ? top_p : 1.f, keys.data(), dev_noise,
+                                        dev_out_tokens, dev_threshold_out, (hipStream_t)stream));
     return SPIRAL_OK;
+}
+
+extern "C" int spiral_sample_truncated(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                                       uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                                       const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                                       void* stream) {
+    return sample_truncated_impl(dev_logits, B, V, temperature, top_k, top_p, seed, host_seq_ids, host_steps, dev_noise,
+                                 dev_out_tokens, dev_threshold_out, nullptr, 0, false, stream);
+}
+
+extern "C" size_t spiral_sample_truncated_workspace_bytes(int B, int V) {
+    if (B < 1 || B > SPIRAL_MAX_BATCH || V < 1) return 0;
+    return sample_truncated_workspace_bytes(B, V);
+}
+
+extern "C" int spiral_sample_truncated_ws(const float* dev_logits, int B, int V, float temperature, int top_k, float top_p,
+                                          uint64_t seed, const int32_t* host_seq_ids, const int32_t* host_steps,
+                                          const float* dev_noise, int32_t* dev_out_tokens, float* dev_threshold_out,
+                                          void* dev_workspace, size_t workspace_bytes, void* stream) {
+    return sample_truncated_impl(dev_logits, B, V, temperature, top_k, top_p, seed, host_seq_ids, host_steps, dev_noise,
+                                 dev_out_tokens, dev_threshold_out, dev_workspace, workspace_bytes, true, stream);
 }

@@ -156,6 +156,12 @@ hipError_t launch_score_objective(const float* logp_new, const float* logp_old, 
 hipError_t launch_sample_truncated(const float* logits, int B, int V, float temperature, int top_k, float top_p,
                                    const uint64_t* host_keys, const float* noise, int32_t* out, float* tau_out,
                                    hipStream_t s);
+// the same thresholds and draw by several workgroups per row and three sweeps; `workspace` holds
+// sample_truncated_workspace_bytes(B, V) bytes
+size_t sample_truncated_workspace_bytes(int B, int V);
+hipError_t launch_sample_truncated_ws(const float* logits, int B, int V, float temperature, int top_k, float top_p,
+                                      const uint64_t* host_keys, const float* noise, int32_t* out, float* tau_out,
+                                      void* workspace, hipStream_t s);
 
 // ---------------------------------------------------------------------------------------------
 // device helpers

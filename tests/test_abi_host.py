@@ -129,6 +129,13 @@ def test_new_entry_points_validate_arguments_without_a_gpu(lib):
     # generated noise needs sequence ids and steps
     assert code(lib.spiral_sample_truncated(fake, 1, 8, 1.0, 2, 0.9, 0, None, None, None, fake, None, None)) == sb.SPIRAL_ERR_INVALID_ARG
     assert code(lib.spiral_sample_truncated(None, 1, 8, 1.0, 2, 0.9, 0, None, None, None, fake, None, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    # workspace variant: null, misaligned or too small workspace; the size query answers 0 for a bad shape
+    need = lib.spiral_sample_truncated_workspace_bytes(4, 50000)
+    assert need > 0 and lib.spiral_sample_truncated_workspace_bytes(0, 50000) == 0 and lib.spiral_sample_truncated_workspace_bytes(4, 0) == 0
+    one = (ctypes.c_int32 * 4)(0, 1, 2, 3)
+    for ws, nbytes in ((None, need), (ctypes.c_void_p(0x10010), need), (fake, need - 1)):
+        assert code(lib.spiral_sample_truncated_ws(fake, 4, 50000, 1.0, 2, 0.9, 0, one, one, None, fake, None, ws, nbytes, None)) == sb.SPIRAL_ERR_INVALID_ARG
+    assert code(lib.spiral_sample_truncated_ws(fake, 4, 50000, 1.0, 2, 1.5, 0, one, one, None, fake, None, fake, need, None)) == sb.SPIRAL_ERR_INVALID_ARG
     # objective: null pointers, negative count, bad clip parameter
     assert code(lib.spiral_policy_objective(None, fake, fake, None, 4, 0.2, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG
     assert code(lib.spiral_policy_objective(fake, fake, fake, None, -1, 0.2, fake, None)) == sb.SPIRAL_ERR_INVALID_ARG

@@ -22,14 +22,21 @@ def sb():
     return binding
 
 
-def _run(sb, logits, T, k, p, seed, ids, steps, noise=None, want_tau=True):
+def _run(sb, logits, T, k, p, seed, ids, steps, noise=None, want_tau=True, ws=False):
+    """ws: the multi-kernel path on a workspace (spiral_sample_truncated_ws) instead of the single kernel"""
     import torch
     B, V = logits.shape
     lg = torch.from_numpy(logits).cuda()
     out = torch.full((B,), -1, dtype=torch.int32, device="cuda")
     tau = torch.zeros(B, dtype=torch.float32, device="cuda") if want_tau else None
     nz = None if noise is None else torch.from_numpy(noise).cuda()
-    sb.spiral_sample_truncated(lg, B, V, T, k, p, seed, ids, steps, nz, out, tau)
+    if ws:
+        need = sb.spiral_sample_truncated_workspace_bytes(B, V)
+        assert need > 0
+        work = torch.full((need,), 0xA5, dtype=torch.uint8, device="cuda")     # the call may not rely on its contents
+        sb.spiral_sample_truncated_ws(lg, B, V, T, k, p, seed, ids, steps, nz, out, tau, work, need)
+    else:
+        sb.spiral_sample_truncated(lg, B, V, T, k, p, seed, ids, steps, nz, out, tau)
     torch.cuda.synchronize()
     return out.cpu().numpy(), (tau.cpu().numpy() if want_tau else None)
 
@@ -38,7 +45,7 @@ SETTINGS = [(0.6, 0, 0.95),        # the paper's evaluation setting
             (1.0, 50, 1.0), (0.8, 20, 0.9), (1.0, 0, 0.5), (1.3, 1, 1.0), (0.6, 3, 0.999), (1.0, 0, 1e-6)]
 
 
-@pytest.mark.parametrize("V", [151936, 1000, 7])
+@pytest.mark.parametrize("V", [151936, 40000, 1000, 7])
 @pytest.mark.parametrize("T,k,p", SETTINGS)
 def test_threshold_and_token_match_oracle(sb, V, T, k, p):
     rng = np.random.default_rng(V + int(1000 * T) + k)
@@ -50,8 +57,13 @@ def test_threshold_and_token_match_oracle(sb, V, T, k, p):
     steps = np.arange(B, dtype=np.int32) * 7
     seed = 99
     noise = np.stack([osamp.gumbel_noise(seed, int(ids[b]), int(steps[b]), V) for b in range(B)])
-    for nz in (noise, None):                                     # shared noise buffer, then the generated stream
-        got_tok, got_tau = _run(sb, logits, T, k, p32, seed, ids, steps, noise=nz)
+    single = {}
+    for nz, ws in ((noise, False), (None, False), (noise, True), (None, True)):   # noise buffer / generated stream; both paths
+        got_tok, got_tau = _run(sb, logits, T, k, p32, seed, ids, steps, noise=nz, ws=ws)
+        if ws:          # the same integers summed in another grouping: every row equal, the undecidable ones included
+            assert np.array_equal(got_tau, single[nz is None][1]) and np.array_equal(got_tok, single[nz is None][0])
+        else:
+            single[nz is None] = (got_tok, got_tau)
         decided = compared = 0
         for b in range(B):
             tok, margin, tau, slack = otr.sample_row(logits[b], T, k, p32, noise[b])
@@ -128,3 +140,38 @@ def test_large_batch_and_argument_errors(sb):
         assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
     with pytest.raises(sb.SpiralError):
         sb.spiral_sample_truncated(lg, B, V, 1.0, 5, 0.9, 0, None, None, None, out, None)
+
+
+def test_workspace_path_large_batch_crowded_rows_and_errors(sb):
+    """More rows than one launch carries keys for; rows whose scores crowd around the cut (all equal, two values, a
+    narrow spread) overflow the candidate list and are done by the single kernel inside the same call."""
+    import torch
+    rng = np.random.default_rng(16)
+    B, V = 131, 20000
+    logits = rng.normal(size=(B, V)).astype(np.float32)
+    logits[5] = 1.25                                             # every score equal
+    logits[6] = np.where(rng.random(V) < 0.5, 0.5, -0.5)        # two values
+    logits[7] = (rng.normal(size=V) * 1e-3).astype(np.float32)  # 20000 scores inside a few bins
+    logits[129] = 3.0
+    ids = np.arange(B, dtype=np.int32); steps = np.arange(B, dtype=np.int32)
+    for T, k, p in ((0.6, 0, 0.95), (1.0, 40, 1.0), (0.8, 9000, 0.9), (1.0, 12000, 1.0)):
+        p32 = float(np.float32(p))
+        a = _run(sb, logits, T, k, p32, 3, ids, steps)
+        b = _run(sb, logits, T, k, p32, 3, ids, steps, ws=True)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), (T, k, p)
+        for r in (0, 5, 6, 7, 127, 128, 129, 130):
+            g = osamp.gumbel_noise(3, r, int(steps[r]), V)
+            tok, margin, tau, slack = otr.sample_row(logits[r], T, k, p32, g)
+            if slack >= SLACK:
+                assert b[1][r] == tau, (T, k, p, r)
+                if margin > MARGIN:
+                    assert b[0][r] == tok
+    lg = torch.from_numpy(logits).cuda()
+    out = torch.empty(B, dtype=torch.int32, device="cuda")
+    need = sb.spiral_sample_truncated_workspace_bytes(B, V)
+    work = torch.empty(need + 256, dtype=torch.uint8, device="cuda")
+    for bad in ((None, need), (work, need - 1), (work[1:], need)):                # null, too small, misaligned
+        with pytest.raises(sb.SpiralError) as e:
+            sb.spiral_sample_truncated_ws(lg, B, V, 0.6, 0, 0.95, 0, ids, steps, None, out, None, bad[0], bad[1])
+        assert e.value.code == sb.SPIRAL_ERR_INVALID_ARG
+    assert sb.spiral_sample_truncated_workspace_bytes(0, V) == 0 and sb.spiral_sample_truncated_workspace_bytes(B, 0) == 0
