@@ -248,7 +248,7 @@ hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hip
     }
     if ((a.K & 31) || (a.N & 3)) return hipErrorInvalidValue;
     // thousands of rows: the 256 x 256 LDS-tiled kernel, once its tiles fill most of the chip
-    if (a.M >= 512 && bn != 1 && gemm_tile_usable(a)) {
+    if (a.M >= 512 && bn != 1 && gemm_tile_usable(a) && (epilogue != EPI_SWIGLU || (a.N & 7) == 0)) {   // SwiGLU rows are stored 8 halves at a time
         const long tiles = (long)((a.M + 255) / 256) * ((a.N + (epilogue == EPI_SWIGLU ? 127 : 255)) / (epilogue == EPI_SWIGLU ? 128 : 256));
         if (tiles >= 200) return launch_gemm_tile(a, epilogue, s);
     }

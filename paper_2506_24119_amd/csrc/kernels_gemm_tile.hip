@@ -38,8 +38,12 @@ constexpr int GROUP_M = 4;
 
 // The weights are the fragment-ordered copies (frag_block(); SWIGLU: the interleaved gate/up matrix, a
 // workgroup covers 128 ffn columns and the epilogue applies SiLU(gate) * up in registers).
-template <bool SWIGLU>
-__global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
+// TEPI: 0 stores the fp32 product, 1 is the SwiGLU epilogue, 2 the q/k/v epilogue (the product never reaches memory:
+// bias, per-head RMSNorm of q and k, RoPE, q stored as half, k and v appended to the sequence's page; head_dim 128,
+// so a wave's 128 columns are exactly one head).
+template <int TEPI>
+__global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs qa) {
+    constexpr bool SWIGLU = TEPI == 1;
     constexpr int J = 4;                            // 32-row weight tiles per wave (and 4 batch tiles)
     constexpr int A_BYTES = TILE_BYTES;             // activation tile; the weight tile follows it
     constexpr int STAGE = STAGE_BYTES;
@@ -97,12 +101,14 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
     // Two register stages: a chunk's global loads are issued two chunks before it is multiplied and
     // one chunk before it is parked in LDS, so the staging writes never wait for memory.
     u32x4 rg[2][16];                                // [stage][8 activation units, 8 weight units]
+    auto load_unit = [&](const int st, const int cc, const int u) {
+        if (u < 8) rg[st][u] = *(const u32x4*)((const uint16_t*)g.A + a_off[u] + (size_t)cc * BK);
+        else rg[st][u] = *(const u32x4*)((const uint16_t*)g.wf + w_off[u - 8] + (size_t)cc * (BK / 16) * 512);
+    };
     auto load = [&](const int st, int c) {
         const int cc = c < NC ? c : NC - 1;           // past the end: a re-read of the last chunk
 #pragma unroll
-        for (int i = 0; i < 8; ++i) rg[st][i] = *(const u32x4*)((const uint16_t*)g.A + a_off[i] + (size_t)cc * BK);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) rg[st][8 + i] = *(const u32x4*)((const uint16_t*)g.wf + w_off[i] + (size_t)cc * (BK / 16) * 512);
+        for (int u = 0; u < 16; ++u) load_unit(st, cc, u);
     };
     auto park_unit = [&](char* buf, const int st, const int u) {
         if (u < 8) *(u32x4*)(buf + dst0 + u * 32 * ROW) = rg[st][u];
@@ -123,7 +129,7 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
         char* other = lds + ((c + 1) & 1) * STAGE;
         u32x4 af[2][4], wf[2][J];
         frags(buf, 0, af[0], wf[0]);
-        load(cu, c + 2);
+        const int cc = c + 2 < NC ? c + 2 : NC - 1;   // past the end: a re-read of the last chunk
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
@@ -131,15 +137,49 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) park_unit(other, nx, ks * 4 + u);
 #pragma unroll
+            for (int u = 0; u < 4; ++u) load_unit(cu, cc, ks * 4 + u);
+#pragma unroll
             for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[j][i] = mma32t(wf[ks & 1][j], af[ks & 1][i], acc[j][i]);
+#ifndef TILE_SCHED
+#define TILE_SCHED 1
+#endif
+#if TILE_SCHED == 1
             if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
+#elif TILE_SCHED == 2
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
+#elif TILE_SCHED == 3
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            }
+#elif TILE_SCHED == 4
+            if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+            }
+#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -161,56 +201,175 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    // ---- epilogue.  In a 32 x 32 tile a lane holds batch row l32 and, in registers 4b..4b+3, weight rows 8b + 4*lh .. +3.
-    if (!SWIGLU) {
+    // ---- epilogue.  In a 32 x 32 tile a lane holds batch row l32 and, in registers 4b..4b+3, weight rows 8b + 4*lh .. +3:
+    //      written straight from there a store instruction touches 64 rows x 16 (or 8) bytes.  Each wave therefore
+    //      turns its tile 32 rows at a time through a private LDS area (the operand buffers are free after the last
+    //      barrier) and stores whole rows: 512 contiguous bytes per half wave (fp32), one 128-byte line per 8 lanes (SwiGLU).
+    if (TEPI == 2) {
+        const int head = (n0 + wn * 128) >> 7;
+        const bool is_q = head < qa.n_q_heads, is_k = !is_q && head < qa.n_q_heads + qa.n_kv_heads;
+        const int kvh = is_q ? 0 : (is_k ? head - qa.n_q_heads : head - qa.n_q_heads - qa.n_kv_heads);
+        const uint16_t* bias = (const uint16_t*)(is_q ? qa.bq : (is_k ? qa.bk : qa.bv));      // bf16 like the weights, or null
+        if (bias) bias += (is_q ? head : kvh) * 128;
+        const float* gain = is_q ? qa.q_gain : (is_k ? qa.k_gain : nullptr);
+        bool bad = false;
+        if (head < qa.n_q_heads + 2 * qa.n_kv_heads) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int m = m0 + wm * 128 + i * 32 + l32;
+                const int mm = m < g.M ? m : g.M - 1;
+                // this lane's 64 values of the head: dimension d = 32 j + 8 b + 4 lh + e sits in acc[j][i][4 b + e]
+                if (bias) {
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const ushort4 bb = *(const ushort4*)(bias + 32 * j + 8 * b + 4 * lh);
+                            acc[j][i][4 * b] += bf16_bits_to_f32(bb.x);
+                            acc[j][i][4 * b + 1] += bf16_bits_to_f32(bb.y);
+                            acc[j][i][4 * b + 2] += bf16_bits_to_f32(bb.z);
+                            acc[j][i][4 * b + 3] += bf16_bits_to_f32(bb.w);
+                        }
+                }
+                if (gain) {
+                    float ss = 0.f;
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) ss += acc[j][i][r] * acc[j][i][r];
+                    ss += __shfl_xor(ss, 32, 64);
+                    const float rs = rsqrtf(ss / 128.f + qa.eps);
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const float4 gg = *(const float4*)(gain + 32 * j + 8 * b + 4 * lh);
+                            acc[j][i][4 * b] = acc[j][i][4 * b] * rs * gg.x;
+                            acc[j][i][4 * b + 1] = acc[j][i][4 * b + 1] * rs * gg.y;
+                            acc[j][i][4 * b + 2] = acc[j][i][4 * b + 2] * rs * gg.z;
+                            acc[j][i][4 * b + 3] = acc[j][i][4 * b + 3] * rs * gg.w;
+                        }
+                }
+                if (is_q || is_k) {                      // rotate-half: d pairs with d + 64, i.e. tile j with tile j + 2
+                    const float2* cs = qa.rope + (size_t)mm * 64;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            const float4 c01 = *(const float4*)(cs + 32 * j + 8 * b + 4 * lh);
+                            const float4 c23 = *(const float4*)(cs + 32 * j + 8 * b + 4 * lh + 2);
+                            const float co[4] = {c01.x, c01.z, c23.x, c23.z}, si[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float lo = acc[j][i][4 * b + e], hi = acc[j + 2][i][4 * b + e];
+                                acc[j][i][4 * b + e] = lo * co[e] - hi * si[e];
+                                acc[j + 2][i][4 * b + e] = hi * co[e] + lo * si[e];
+                            }
+                        }
+                }
+                if (m < g.M) {
+                    uint16_t* dst;
+                    int slot = 0;
+                    if (is_q) {
+                        dst = qa.q + ((size_t)m * qa.n_q_heads + head) * 128;
+                    } else {
+                        const int pos = qa.row_pos[m];
+                        const int page = qa.block_table[(size_t)qa.row_seq[m] * qa.max_blocks + (pos >> 4)];
+                        slot = pos & (kPageTokens - 1);
+                        dst = qa.pages + ((size_t)page * qa.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * 128) +
+                              (is_k ? 0 : kPageTokens * 128);
+                    }
+#pragma unroll
+                    for (int j = 0; j < J; ++j)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b) {
+                            ushort4 o;
+                            o.x = f32_to_act16_noting(acc[j][i][4 * b], bad);
+                            o.y = f32_to_act16_noting(acc[j][i][4 * b + 1], bad);
+                            o.z = f32_to_act16_noting(acc[j][i][4 * b + 2], bad);
+                            o.w = f32_to_act16_noting(acc[j][i][4 * b + 3], bad);
+                            if (is_q) {
+                                *(ushort4*)(dst + 32 * j + 8 * b + 4 * lh) = o;
+                            } else if (is_k) {
+                                // K element (token, d) sits at (d/32)*512 + (((d%32)/8)*16 + token)*8 + d%8; d%32 = 8 b + 4 lh + e
+                                *(ushort4*)(dst + j * 512 + ((b * 16 + slot) << 3) + 4 * lh) = o;
+                            } else {
+                                // V element (d, token) sits at (d/32)*512 + ((token/4)*16 + d%16)*8 + ((d/16)%2)*4 + token%4
+                                uint16_t* vb = dst + j * 512 + (((slot >> 2) * 16 + 8 * (b & 1) + 4 * lh) << 3) + ((b >> 1) << 2) + (slot & 3);
+                                vb[0] = o.x; vb[8] = o.y; vb[16] = o.z; vb[24] = o.w;
+                            }
+                        }
+                }
+            }
+        }
+        report_saturation(qa.sat_count, bad);
+    } else if (!SWIGLU) {
         float* out = (float*)g.out;
+        constexpr int TROW = 128 * 4 + 16;              // staged row: 128 floats + pad
+        char* tb = lds + wave * (32 * TROW);
+        const int rr = lane >> 5, c4 = lane & 31;       // read side: row 2 p + rr, floats 4 c4 .. 4 c4 + 3
+        const int n = n0 + wn * 128 + 4 * c4;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int m = m0 + wm * 128 + i * 32 + l32;
 #pragma unroll
             for (int j = 0; j < J; ++j)
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int n = n0 + (wn * J + j) * 32 + 8 * b + 4 * lh;
-                    if (m < g.M && n < g.N)
-                        *(float4*)(out + (size_t)m * g.N + n) =
-                            make_float4(acc[j][i][4 * b], acc[j][i][4 * b + 1], acc[j][i][4 * b + 2], acc[j][i][4 * b + 3]);
-                }
+                for (int b = 0; b < 4; ++b)
+                    *(float4*)(tb + l32 * TROW + (j * 32 + 8 * b + 4 * lh) * 4) =
+                        make_float4(acc[j][i][4 * b], acc[j][i][4 * b + 1], acc[j][i][4 * b + 2], acc[j][i][4 * b + 3]);
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ps = 0; ps < 16; ++ps) {
+                const int row = 2 * ps + rr;
+                const float4 v = *(const float4*)(tb + row * TROW + c4 * 16);
+                const int m = m0 + wm * 128 + i * 32 + row;
+                if (m < g.M && n < g.N) *(float4*)(out + (size_t)m * g.N + n) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     } else {
         bool bad = false;
+        constexpr int TROW = 64 * 2 + 16;               // staged row: 64 halves + pad
+        char* tb = lds + wave * (32 * TROW);
+        const int rr = lane >> 3, c8 = lane & 7;        // read side: row 8 p + rr, halves 8 c8 .. 8 c8 + 7
+        const int f = n0 + wn * 64 + 8 * c8;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int m = m0 + wm * 128 + i * 32 + l32;
 #pragma unroll
             for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int b = 0; b < 2; ++b) {
-                    const int f = n0 + (wn * J + j) * 16 + 8 * b + 4 * lh;
-                    if (m < g.M && f < g.N) {
-                        ushort4 o;
-                        o.x = f32_to_act16_noting(silu_f(acc[j][i][4 * b]) * acc[j][i][4 * b + 8], bad);
-                        o.y = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 1]) * acc[j][i][4 * b + 9], bad);
-                        o.z = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 2]) * acc[j][i][4 * b + 10], bad);
-                        o.w = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 3]) * acc[j][i][4 * b + 11], bad);
-                        *(ushort4*)((uint16_t*)g.out + (size_t)m * g.N + f) = o;
-                    }
+                    ushort4 o;
+                    o.x = f32_to_act16_noting(silu_f(acc[j][i][4 * b]) * acc[j][i][4 * b + 8], bad);
+                    o.y = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 1]) * acc[j][i][4 * b + 9], bad);
+                    o.z = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 2]) * acc[j][i][4 * b + 10], bad);
+                    o.w = f32_to_act16_noting(silu_f(acc[j][i][4 * b + 3]) * acc[j][i][4 * b + 11], bad);
+                    *(ushort4*)(tb + l32 * TROW + (j * 16 + 8 * b + 4 * lh) * 2) = o;
                 }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int ps = 0; ps < 4; ++ps) {
+                const int row = 8 * ps + rr;
+                const u32x4 v = *(const u32x4*)(tb + row * TROW + c8 * 16);
+                const int m = m0 + wm * 128 + i * 32 + row;
+                if (m < g.M && f < g.N) *(u32x4*)((uint16_t*)g.out + (size_t)m * g.N + f) = v;
+            }
+            __builtin_amdgcn_wave_barrier();
         }
         report_saturation(g.sat_count, bad);
     }
 }
 
-template <bool SWIGLU>
-static hipError_t launch_tile(const GemmArgs& a, hipStream_t s) {
-    const int cols = SWIGLU ? 128 : 256;
+template <int TEPI>
+static hipError_t launch_tile(const GemmArgs& a, const QkvPostArgs& qa, hipStream_t s) {
+    const int cols = TEPI == 1 ? 128 : 256;
     const int m_tiles = (a.M + BM - 1) / BM;
     const int n_tiles = (a.N + cols - 1) / cols;
     const int per_xcd = (m_tiles * n_tiles + 7) / 8;
     const size_t lds_bytes = (size_t)2 * STAGE_BYTES;
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_tile_kernel<TEPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((gemm_tile_kernel<SWIGLU>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a);
+    hipLaunchKernelGGL((gemm_tile_kernel<TEPI>), dim3(per_xcd * 8), dim3(256), lds_bytes, s, a, qa);
     return hipGetLastError();
 }
 
@@ -221,8 +380,21 @@ bool gemm_tile_usable(const GemmArgs& a) {
 }
 
 hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, hipStream_t s) {
-    if (!gemm_tile_usable(a)) return hipErrorInvalidValue;
-    return epilogue == EPI_SWIGLU ? launch_tile<true>(a, s) : launch_tile<false>(a, s);
+    if (!gemm_tile_usable(a) || (epilogue == EPI_SWIGLU && (a.N & 7))) return hipErrorInvalidValue;
+    const QkvPostArgs none = {};
+    return epilogue == EPI_SWIGLU ? launch_tile<1>(a, none, s) : launch_tile<0>(a, none, s);
+}
+
+// The q/k/v projection with the work of qkv_post_kernel in its epilogue (qa.qkv and qa.n_part are not used).
+bool gemm_tile_qkv_usable(const GemmArgs& a, const QkvPostArgs& qa, bool w_bf16) {
+    const long tiles = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+    return w_bf16 && a.M >= 512 && tiles >= 200 && gemm_tile_usable(a) && qa.hd == 128 && (a.N & 255) == 0 &&
+           a.N == (qa.n_q_heads + 2 * qa.n_kv_heads) * 128;
+}
+
+hipError_t launch_gemm_tile_qkv(const GemmArgs& a, const QkvPostArgs& qa, hipStream_t s) {
+    if (!gemm_tile_qkv_usable(a, qa, true)) return hipErrorInvalidValue;
+    return launch_tile<2>(a, qa, s);
 }
 
 }  // namespace spiral

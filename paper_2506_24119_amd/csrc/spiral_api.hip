@@ -52,6 +52,7 @@ struct Tune {
     int chunk_pages = 16;          // decode attention: least (row, kv head, page) units per workgroup
     int attn_wgs = 0;              // workgroups of the decode attention; 0 = 3 per compute unit (its occupancy)
     int frag = 1;                  // 0: ignore spiral_model_repack (weights stay row-major; for A/B measurements)
+    int fuse_qkv = 1;              // 0: large-M q/k/v projection and its post-processing as two kernels (for A/B measurements)
     int fail_after = 0;            // test hook: the n-th timed launch from now reports a launch failure instead of running
 };
 constexpr int kMaxSplit = 16;
@@ -112,6 +113,7 @@ static void parse_tune(Tune& t, const char* e) {
                 else if (k == "chunk") { t.chunk_pages = a; }
                 else if (k == "wgs") { t.attn_wgs = a; }
                 else if (k == "frag") { t.frag = a; }
+                else if (k == "fuse_qkv") { t.fuse_qkv = a; }
                 else if (k == "fail_after") { t.fail_after = a; }
             }
         }
@@ -632,14 +634,19 @@ static int run_layers(StepCtx& c) {
         g.rows[0] = qw; g.rows[1] = kw; g.rows[2] = kw;
         g.M = c.rows; g.N = nqkv; g.K = d; g.out = c.w.qkv; g.splits = s_qkv;
         g.wf = m->f_lm ? m->f_qkv[l] : nullptr;
-        HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, sh_qkv.bn, c.s); }));
-
         uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
         QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
                           (const float*)m->lw(l, SPIRAL_W_Q_NORM), (const float*)m->lw(l, SPIRAL_W_K_NORM),
                           c.w.rope, c.w.row_seq, c.w.row_pos, c.p->d_block_table, c.w.q, pages,
                           c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps, sat};
-        HIP_TRY(timed(m, SPIRAL_K_QKV_POST, c.s, [&] { return launch_qkv_post(qa, m->w_bf16, c.s); }));
+        if (t.fuse_qkv && s_qkv == 1 && sh_qkv.bn != 1 && gemm_tile_qkv_usable(g, qa, m->w_bf16)) {
+            // thousands of rows (prefill, scoring): the projection's epilogue does the post-processing, the fp32 product
+            // never reaches memory
+            HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm_tile_qkv(g, qa, c.s); }));
+        } else {
+            HIP_TRY(timed(m, SPIRAL_K_GEMM_QKV, c.s, [&] { return launch_gemm(g, EPI_STORE_F32, m->w_bf16, sh_qkv.bn, c.s); }));
+            HIP_TRY(timed(m, SPIRAL_K_QKV_POST, c.s, [&] { return launch_qkv_post(qa, m->w_bf16, c.s); }));
+        }
 
         AttnArgs aa = {};
         aa.q = c.w.q; aa.pages = pages; aa.block_table = c.p->d_block_table; aa.row_seq = c.w.row_seq;

@@ -121,6 +121,8 @@ hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, int epilogue, bool w_bf16, int bn, hipStream_t s);
 bool gemm_tile_usable(const GemmArgs& a);                                                  // fragment-ordered weights, K % 64 == 0, ...
 hipError_t launch_gemm_tile(const GemmArgs& a, int epilogue, hipStream_t s);
+bool gemm_tile_qkv_usable(const GemmArgs& a, const QkvPostArgs& qa, bool w_bf16);          // ... and head_dim 128, whole heads per tile
+hipError_t launch_gemm_tile_qkv(const GemmArgs& a, const QkvPostArgs& qa, hipStream_t s);  // q/k/v projection + qkv_post in one kernel
 hipError_t launch_gemm_stream(const GemmArgs& a, int epilogue, int bn, hipStream_t s);   // K % 128 == 0, N % 16 == 0
 hipError_t launch_attn_stream(const AttnArgs& a, int hd, bool act32, hipStream_t s);
 hipError_t launch_attn_stream_combine(const AttnArgs& a, int hd, bool act32, hipStream_t s);
