@@ -337,10 +337,28 @@ __global__ __launch_bounds__(HD) void attn_stream_combine_kernel(AttnArgs a) {
     const int n_parts = last - first + 1;
     const float* base = a.part + (((size_t)r * Hkv + kvh) * a.n_chunks * G + j) * (HD + 2);
     const size_t cstride = (size_t)G * (HD + 2);
+    // the first four parts (nearly always all of them) are requested at once instead of one after the other
+    constexpr int PRE = 4;
+    float pm[PRE], pl[PRE], po[PRE];
+#pragma unroll
+    for (int c = 0; c < PRE; ++c) {
+        const float* src = base + (size_t)(c < n_parts ? c : n_parts - 1) * cstride;
+        pm[c] = src[HD]; pl[c] = src[HD + 1]; po[c] = src[i];
+    }
     float M = kNegBig;
-    for (int c = 0; c < n_parts; ++c) M = fmaxf(M, base[c * cstride + HD]);
+#pragma unroll
+    for (int c = 0; c < PRE; ++c)
+        if (c < n_parts) M = fmaxf(M, pm[c]);
+    for (int c = PRE; c < n_parts; ++c) M = fmaxf(M, base[c * cstride + HD]);
     float L = 0.f, O = 0.f;
-    for (int c = 0; c < n_parts; ++c) {
+#pragma unroll
+    for (int c = 0; c < PRE; ++c)
+        if (c < n_parts) {
+            const float sc = __builtin_amdgcn_exp2f(pm[c] - M);
+            L += pl[c] * sc;
+            O += po[c] * sc;
+        }
+    for (int c = PRE; c < n_parts; ++c) {
         const float sc = __builtin_amdgcn_exp2f(base[c * cstride + HD] - M);
         L += base[c * cstride + HD + 1] * sc;
         O += base[c * cstride + i] * sc;

@@ -273,10 +273,9 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs 
                     if (is_q) {
                         dst = qa.q + ((size_t)m * qa.n_q_heads + head) * 128;
                     } else {
-                        const int pos = qa.row_pos[m];
-                        const int page = qa.block_table[(size_t)qa.row_seq[m] * qa.max_blocks + (pos >> 4)];
-                        slot = pos & (kPageTokens - 1);
-                        dst = qa.pages + ((size_t)page * qa.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * 128) +
+                        const int2 pp = qa.row_page[m];
+                        slot = pp.y & (kPageTokens - 1);
+                        dst = qa.pages + ((size_t)pp.x * qa.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * 128) +
                               (is_k ? 0 : kPageTokens * 128);
                     }
 #pragma unroll

@@ -143,6 +143,8 @@ __global__ __launch_bounds__(256) void embed_norm_kernel(EmbedArgs a, RopeFreq f
         double ang = (double)pos * f.inv_freq[threadIdx.x];
         a.rope[(size_t)r * a.half_hd + threadIdx.x] = make_float2((float)cos(ang), (float)sin(ang));
     }
+    if (threadIdx.x == 255)
+        a.row_page[r] = make_int2(a.block_table[(size_t)a.row_seq[r] * a.max_blocks + (pos >> 4)], pos);
     int tok = a.tokens[r];
     tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);   // ids are validated by the caller; stay in bounds regardless
     float* x = a.x + (size_t)r * a.d;
@@ -183,12 +185,13 @@ __global__ __launch_bounds__(1024) void add_norm_wide_kernel(NormArgs a) {
     const size_t pstride = (size_t)a.rows_in * a.d;
     const float* prow = a.part + (size_t)ri * a.d;
     const int groups = a.d >> 2;
-    float4 v[2];
+    float4 v[2], gn[2];
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int gidx = threadIdx.x + j * blockDim.x;
         v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        gn[j] = *(const float4*)(a.gain + (gidx < groups ? gidx : groups - 1) * 4);     // with the other loads, not behind the barrier
         if (gidx < groups) {
             const int i = gidx * 4;
             float4 acc = *(const float4*)(x + i);
@@ -220,12 +223,11 @@ __global__ __launch_bounds__(1024) void add_norm_wide_kernel(NormArgs a) {
         const int gidx = threadIdx.x + j * blockDim.x;
         if (gidx < groups) {
             const int i = gidx * 4;
-            const float4 gn = *(const float4*)(a.gain + i);
             const size_t o = (size_t)ro * a.d + i;
-            ActStore<ACT32>::put_noting(a.h, o, v[j].x * rs * gn.x, bad);
-            ActStore<ACT32>::put_noting(a.h, o + 1, v[j].y * rs * gn.y, bad);
-            ActStore<ACT32>::put_noting(a.h, o + 2, v[j].z * rs * gn.z, bad);
-            ActStore<ACT32>::put_noting(a.h, o + 3, v[j].w * rs * gn.w, bad);
+            ActStore<ACT32>::put_noting(a.h, o, v[j].x * rs * gn[j].x, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 1, v[j].y * rs * gn[j].y, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 2, v[j].z * rs * gn[j].z, bad);
+            ActStore<ACT32>::put_noting(a.h, o + 3, v[j].w * rs * gn[j].w, bad);
         }
     }
     report_saturation(a.sat_count, bad);
@@ -275,7 +277,10 @@ hipError_t launch_add_norm(const NormArgs& a, bool act32, hipStream_t s) {
 // sequence's page in MFMA operand order (layout in kernels_attn.hip).
 // One wave per (row, head); lane p handles the pair (p, p + hd/2).
 // ---------------------------------------------------------------------------------------------
-template <bool WBF16>
+// NP: the number of partials the kernel is built for (>= a.n_part).  Every load of a lane - partials, bias, gains,
+// rotation, page look-up - is issued before the first use and none sits behind a branch: written as a loop over the
+// partials the compiler waits for each pair before it requests the next, nine dependent round trips per wave.
+template <bool WBF16, int NP>
 __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
     const int r = blockIdx.x;
     const int head = blockIdx.y * 4 + (threadIdx.x >> 6);
@@ -292,43 +297,47 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
     const int bias_off = (is_q ? head : kvh) * hd;
     const float* gain = is_q ? a.q_gain : (is_k ? a.k_gain : nullptr);
 
-    const int pos = a.row_pos[r];
-    const int seq = a.row_seq[r];
-    const int slot = pos & (kPageTokens - 1);
-    size_t page_base = 0;
-    if (!is_q) {
-        const int page = a.block_table[(size_t)seq * a.max_blocks + (pos >> 4)];
-        page_base = ((size_t)page * a.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * hd);
-    }
+    const int2 pp = a.row_page[r];                       // (page, position): q heads read it too and ignore it
+    const int slot = pp.y & (kPageTokens - 1);
+    const size_t page_base = ((size_t)pp.x * a.n_kv_heads + kvh) * (size_t)(2 * kPageTokens * hd);
 
     bool bad = false;
     for (int p = lane; p < ((half + 63) & ~63); p += 64) {
         const bool act = p < half;
-        float lo = 0.f, hi = 0.f;
-        if (act) {
-            for (int s = 0; s < a.n_part; ++s) {
-                const float* src = a.qkv + ((size_t)s * a.n_rows + r) * width + (size_t)head * hd;
-                lo += src[p];
-                hi += src[p + half];
-            }
-            if (bias) {
-                if (WBF16) {
-                    lo += bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + p]);
-                    hi += bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + p + half]);
-                } else {
-                    lo += ((const float*)bias)[bias_off + p];
-                    hi += ((const float*)bias)[bias_off + p + half];
-                }
+        const int pc = act ? p : half - 1;              // idle lanes re-read the last pair
+        float pl[NP], ph[NP];
+#pragma unroll
+        for (int s = 0; s < NP; ++s) {
+            const int sc = s < a.n_part ? s : a.n_part - 1;
+            const float* src = a.qkv + ((size_t)sc * a.n_rows + r) * width + (size_t)head * hd;
+            pl[s] = src[pc];
+            ph[s] = src[pc + half];
+        }
+        float b_lo = 0.f, b_hi = 0.f, g_lo = 1.f, g_hi = 1.f;
+        if (bias) {                                     // uniform over the wave
+            if (WBF16) {
+                b_lo = bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + pc]);
+                b_hi = bf16_bits_to_f32(((const uint16_t*)bias)[bias_off + pc + half]);
+            } else {
+                b_lo = ((const float*)bias)[bias_off + pc];
+                b_hi = ((const float*)bias)[bias_off + pc + half];
             }
         }
+        if (gain) { g_lo = gain[pc]; g_hi = gain[pc + half]; }
+        const float2 cs = a.rope[(size_t)r * half + pc];
+        float lo = 0.f, hi = 0.f;
+#pragma unroll
+        for (int s = 0; s < NP; ++s)
+            if (s < a.n_part) { lo += pl[s]; hi += ph[s]; }
+        if (bias) { lo += b_lo; hi += b_hi; }
+        if (!act) { lo = 0.f; hi = 0.f; }
         if (gain) {       // hd <= 128: the whole head sits in one pass of the wave
             const float ss = wave_sum(lo * lo + hi * hi);
             const float rs = rsqrtf(ss / (float)hd + a.eps);
-            if (act) { lo = lo * rs * gain[p]; hi = hi * rs * gain[p + half]; }
+            lo = lo * rs * g_lo; hi = hi * rs * g_hi;
         }
         if (!act) continue;
         if (is_q || is_k) {
-            const float2 cs = a.rope[(size_t)r * half + p];
             const float nlo = lo * cs.x - hi * cs.y;
             const float nhi = hi * cs.x + lo * cs.y;
             lo = nlo; hi = nhi;
@@ -354,11 +363,20 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs a) {
     report_saturation(a.sat_count, bad);
 }
 
+template <int NP>
+static void launch_qkv_post_np(const QkvPostArgs& a, bool w_bf16, dim3 g, hipStream_t s) {
+    if (w_bf16) hipLaunchKernelGGL((qkv_post_kernel<true, NP>), g, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((qkv_post_kernel<false, NP>), g, dim3(256), 0, s, a);
+}
+
 hipError_t launch_qkv_post(const QkvPostArgs& a, bool w_bf16, hipStream_t s) {
     const int n_heads = a.n_q_heads + 2 * a.n_kv_heads;
-    dim3 g(a.n_rows, (n_heads + 3) / 4), b(256);
-    if (w_bf16) hipLaunchKernelGGL((qkv_post_kernel<true>), g, b, 0, s, a);
-    else hipLaunchKernelGGL((qkv_post_kernel<false>), g, b, 0, s, a);
+    if (a.n_part < 1 || a.n_part > 16 || a.hd < 2) return hipErrorInvalidValue;
+    dim3 g(a.n_rows, (n_heads + 3) / 4);
+    if (a.n_part == 1) launch_qkv_post_np<1>(a, w_bf16, g, s);
+    else if (a.n_part <= 5) launch_qkv_post_np<5>(a, w_bf16, g, s);
+    else if (a.n_part <= 8) launch_qkv_post_np<8>(a, w_bf16, g, s);
+    else launch_qkv_post_np<16>(a, w_bf16, g, s);
     return hipGetLastError();
 }
 

@@ -341,6 +341,7 @@ struct Workspace {
     float* x; void* h; float* qkv; uint16_t* q; void* o; float* proj; void* mlp; void* hf;
     float* attn_part; float2* rope;
     int32_t *row_seq, *row_pos, *seq_ids, *cu_rows, *base_pos, *last_rows, *page_start;
+    int2* row_page;                           // (page, position) that takes each row's k and v
     float *score_part, *score_tgt;
     uint64_t* s_keys; float2* s_part;         // fused sampler: row keys, per-tile winners
     size_t bytes;
@@ -385,6 +386,7 @@ static Workspace carve(const spiral_model* m, char* base, int rows, int max_cont
     w.rope = (float2*)take(R * (c.head_dim / 2) * 8);
     w.row_seq = (int32_t*)take(R * 4);
     w.row_pos = (int32_t*)take(R * 4);
+    w.row_page = (int2*)take(R * 8);
     w.attn_part = (float*)take(brows * c.n_kv_heads * decode_slots(m, max_context) * G * (c.head_dim + 2) * 4);
     w.score_part = (float*)take(R * kScoreSplits * 8);
     w.score_tgt = (float*)take(R * 4);
@@ -637,8 +639,8 @@ static int run_layers(StepCtx& c) {
         uint16_t* pages = c.p->d_pages + (size_t)l * c.p->layer_elems;
         QkvPostArgs qa = {c.w.qkv, m->lw(l, SPIRAL_W_BQ), m->lw(l, SPIRAL_W_BK), m->lw(l, SPIRAL_W_BV),
                           (const float*)m->lw(l, SPIRAL_W_Q_NORM), (const float*)m->lw(l, SPIRAL_W_K_NORM),
-                          c.w.rope, c.w.row_seq, c.w.row_pos, c.p->d_block_table, c.w.q, pages,
-                          c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, c.p->max_blocks, cfg.rms_eps, sat};
+                          c.w.rope, c.w.row_page, c.w.q, pages,
+                          c.rows, s_qkv, cfg.n_q_heads, cfg.n_kv_heads, hd, cfg.rms_eps, sat};
         if (t.fuse_qkv && s_qkv == 1 && sh_qkv.bn != 1 && gemm_tile_qkv_usable(g, qa, m->w_bf16)) {
             // thousands of rows (prefill, scoring): the projection's epilogue does the post-processing, the fp32 product
             // never reaches memory
@@ -773,7 +775,8 @@ static int prefill_or_score(spiral_model* m, spiral_kv_pool* p, const int32_t* h
         HIP_TRY(launch_upload_multi(dst, src, cnt, 4, s));
         HIP_TRY(launch_prefill_meta(w.cu_rows, w.base_pos, w.seq_ids, B, (int)rows, w.row_seq, w.row_pos, s));
         EmbedArgs e = {dev_tokens_packed, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h,
-                       w.row_pos, w.rope, (int)rows, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps};
+                       w.row_pos, w.rope, (int)rows, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps,
+                       w.row_seq, p->d_block_table, p->max_blocks, w.row_page};
         HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
         StepCtx c = {m, p, w, s, (int)rows, B, false, max_new, 1, dev_logits};
         c.score_targets = dev_targets;
@@ -874,7 +877,8 @@ static int decode_impl(spiral_model* m, spiral_kv_pool* p, const int32_t* host_s
         const int cnt[4] = {B, B, B + 1, (int)keys.size()};
         HIP_TRY(launch_upload_multi(dst, src, cnt, keys.empty() ? 3 : 4, s));
         EmbedArgs e = {dev_in_tokens, m->w[0], (const float*)m->lw(0, SPIRAL_W_ATTN_NORM), w.x, w.h,
-                       w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps};
+                       w.row_pos, w.rope, B, m->cfg.d_model, m->cfg.head_dim / 2, m->cfg.vocab, m->cfg.rms_eps,
+                       w.row_seq, p->d_block_table, p->max_blocks, w.row_page};
         HIP_TRY(launch_embed_norm(e, m->freq, m->w_bf16, !m->w_bf16, s));
         StepCtx c = {m, p, w, s, B, B, true, 1, decode_chunks(m, max_ctx), dev_logits};
         {

@@ -88,6 +88,9 @@ struct EmbedArgs {
     float2* rope;             // [rows][hd/2] (cos, sin), written
     int32_t n_rows, d, half_hd, vocab;
     float eps;
+    // the page that takes each row's k and v, looked up here once for all layers: row_page[r] = (page, position)
+    const int32_t* row_seq; const int32_t* block_table; int32_t max_blocks;
+    int2* row_page;           // [rows], written
 };
 hipError_t launch_embed_norm(const EmbedArgs& a, const RopeFreq& f, bool w_bf16, bool act32, hipStream_t s);
 
@@ -108,11 +111,10 @@ struct QkvPostArgs {
     const void* bq; const void* bk; const void* bv;   // weight dtype, or null
     const float* q_gain; const float* k_gain;         // [hd] or null
     const float2* rope;       // [rows][hd/2]
-    const int32_t* row_seq; const int32_t* row_pos;
-    const int32_t* block_table;
-    uint16_t* q;              // bf16 [rows][Hq][hd]
+    const int2* row_page;     // [rows] (physical page, position) of the row's token, from embed_norm_kernel
+    uint16_t* q;              // half [rows][Hq][hd]
     uint16_t* pages;          // this layer's pages
-    int32_t n_rows, n_part, n_q_heads, n_kv_heads, hd, max_blocks;
+    int32_t n_rows, n_part, n_q_heads, n_kv_heads, hd;
     float eps;
     int32_t* sat_count;       // or null
 };
