@@ -59,29 +59,35 @@ __device__ __forceinline__ uint64_t shfl_down_u64(uint64_t v, int d) {
     return ((uint64_t)hi << 32) | lo;
 }
 
+// 2^(j/32), j = 0..31
+__device__ const double kExp2Tab[32] = {
+    1.0, 1.0218971486541166, 1.0442737824274138, 1.0671404006768237,
+    1.0905077326652577, 1.1143867425958924, 1.1387886347566916, 1.1637248587775775,
+    1.189207115002721, 1.215247359980469, 1.241857812073484, 1.2690509571917332,
+    1.2968395546510096, 1.3252366431597413, 1.3542555469368927, 1.383909881963832,
+    1.4142135623730951, 1.4451808069770467, 1.4768261459394993, 1.5091644275934228,
+    1.5422108254079407, 1.5759808451078865, 1.6104903319492543, 1.645755478153965,
+    1.681792830507429, 1.718619298122478, 1.7562521603732995, 1.7947090750031072,
+    1.8340080864093424, 1.8741676341103, 1.9152065613971474, 1.9571441241754002};
+
 // floor(exp(z - zmax) * 2^45) for z <= zmax; zero from 32 below the maximum on (exp(-32) * 2^45 < 1) and for
-// z = -inf.  Argument reduction by ln 2 and the Taylor series to the 13th power of |r| <= 0.347 (remainder 4e-18).
+// z = -inf.  exp(x) = 2^(k/32) * exp(r) with k = round(32 x / ln 2): the table gives 2^((k mod 32)/32), the Taylor
+// series to the 6th power exp(r) for |r| <= ln 2 / 64 (remainder 4e-18), ldexp the rest; 4e-16 of exp() at worst.
 __device__ __forceinline__ uint64_t mass45(float z, float zmax) {
     const double x = (double)z - (double)zmax;
     if (!(x > -32.0)) return 0;
-    const double k = rint(x * 1.4426950408889634);
-    double r = fma(-k, 6.93147180369123816490e-01, x);
-    r = fma(-k, 1.90821492927058770002e-10, r);
-    double p = 1.6059043836821613e-10;            // 1/13!
-    p = fma(p, r, 2.08767569878681e-09);          // 1/12!
-    p = fma(p, r, 2.505210838544172e-08);         // 1/11!
-    p = fma(p, r, 2.755731922398589e-07);         // 1/10!
-    p = fma(p, r, 2.7557319223985893e-06);        // 1/9!
-    p = fma(p, r, 2.48015873015873e-05);          // 1/8!
-    p = fma(p, r, 1.984126984126984e-04);         // 1/7!
-    p = fma(p, r, 1.388888888888889e-03);         // 1/6!
-    p = fma(p, r, 8.333333333333333e-03);         // 1/5!
-    p = fma(p, r, 4.1666666666666664e-02);        // 1/4!
-    p = fma(p, r, 1.6666666666666666e-01);        // 1/3!
+    const double k = rint(x * 46.16624130844683);
+    double r = fma(-k, 0.021660849392489467, x);       // ln 2 / 32, high part (12 trailing zero bits: k * hi is exact)
+    r = fma(-k, 8.823528300947368e-15, r);             // low part
+    double p = 1.0 / 720.0;
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
     p = fma(p, r, 0.5);
     p = fma(p, r, 1.0);
     p = fma(p, r, 1.0);
-    return (uint64_t)ldexp(p, (int)k + 45);
+    const int ki = (int)k;                              // <= 0
+    return (uint64_t)ldexp(kExp2Tab[ki & 31] * p, (ki >> 5) + 45);
 }
 
 constexpr int kBins = 4096;           // linear in zmax - z, 1/128 wide; the last one is everything >= 32 below the maximum
