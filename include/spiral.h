@@ -117,6 +117,7 @@ int spiral_model_repack(spiral_model* m, void* dev_buffer, size_t bytes, void* s
  * spec is a comma-separated list of key=value items (unknown keys are ignored): "qkv=R:S", "o=R:S", "down=R:S"
  * (weight rows per workgroup : K splits of that projection), "gu=R", "lm=R", "chunk=P" (least pages per
  * decode-attention workgroup), "wgs=N" (workgroups of the decode attention), "frag=0|1" (use the repacked weights),
+ * "fuse_qkv=0|1" (large row counts: q/k/v post-processing inside the projection kernel or as its own kernel),
  * "fail_after=N" (error-path tests: the N-th
  * kernel launch of the layer stack from now on is not made and reports a launch failure).  Results stay within
  * the parity tolerance for every setting; the defaults are the measured best.  "frag" must be set before

@@ -216,6 +216,37 @@ def test_repacked_weights_give_bit_identical_logits(sb):
     assert np.array_equal(outs[0][1], outs[1][1])
 
 
+@pytest.mark.parametrize("variant", ["qk_norm", "qkv_bias"])
+def test_large_prefill_with_the_qkv_epilogue_in_the_projection(sb, variant):
+    """A prefill of ~2,500 rows on a wide q/k/v projection (50 heads of 128) takes the 256 x 256 tiled kernel whose
+    epilogue does the bias / per-head norm / RoPE / page append itself; the same call with that fusion switched off
+    (spiral_model_tune "fuse_qkv=0": projection, then qkv_post_kernel) must agree to rounding, a page written by the
+    epilogue must serve the decode steps that follow, and one sequence is compared with the oracle."""
+    g = si.ModelGeometry("wide-qkv", 2, 256, 40, 5, 128, 512, 1500, 1e6,
+                         qk_norm=(variant == "qk_norm"), qkv_bias=(variant == "qkv_bias"))
+    w = si.make_weights(g, seed=31)
+    prompts = si.make_prompts(g.vocab, 6, 300, 520, seed=17)
+    prompts[0] = prompts[0][:271]                                   # ends inside a page
+    forced = si.make_forced_tokens(g.vocab, 6, 4, seed=18)
+    outs = []
+    for tune in ("fuse_qkv=1", "fuse_qkv=0"):
+        sess = make_session(sb, g, w, n_pages=256, max_seqs=8, max_blocks=40, max_rows=4096, max_context=640, page_seed=12, tune=tune)
+        assert sess.repacked is not None
+        # which path ran: the post-processing kernel is launched once per layer and decode step, and once per layer
+        # more by the prefill when the projection does not do its work
+        sb.spiral_profile_begin(sess.model, sb.KERNEL_CLASSES.index("qkv_post"), 1000)
+        logits, _ = run_teacher_forced(sb, sess, g, prompts, forced)
+        _, n_post = sb.spiral_profile_end(sess.model)
+        assert n_post == g.n_layers * (forced.shape[0] + (0 if tune == "fuse_qkv=1" else 1)), (tune, n_post)
+        assert sess.saturation_count() == 0
+        outs.append(logits)
+        sess.close()
+    scale = np.abs(outs[1]).max()
+    assert np.abs(outs[0] - outs[1]).max() <= 2e-3 * scale         # same arithmetic, another summation order in the norm
+    want = oracle_teacher_forced(g, w, prompts[0], forced[:, 0])
+    assert_logits_close(outs[0][:, 0], want, f"wide-qkv {variant} seq 0")
+
+
 # ------------------------------------------------------------------------------------------------
 # invariants of the path itself
 # ------------------------------------------------------------------------------------------------
