@@ -346,6 +346,7 @@ __global__ __launch_bounds__(kThreads) void trunc_plan_kernel(int V, float tempe
                                                               const uint32_t* hist_cnt, TruncRow* rows) {
     __shared__ uint64_t w_mass[kWaves];
     __shared__ uint32_t w_cnt[kWaves];
+    __shared__ int s_found;
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint64_t bm[4];
     uint32_t bc[4];
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void trunc_plan_kernel(int V, float tempe
         if (lane >= d) { im += om; ic += oc; }
     }
     if (lane == 63) { w_mass[wave] = im; w_cnt[wave] = ic; }
-    if (tid == 0) rows[row].fallback = 1;                   // stands if no bin qualifies (a row of NaN)
+    if (tid == 0) s_found = 0;
     __syncthreads();
     uint64_t before_m = im - tm, total_m = 0;
     uint32_t before_c = ic - tc;
@@ -411,9 +412,16 @@ __global__ __launch_bounds__(kThreads) void trunc_plan_kernel(int V, float tempe
             }
             r.fallback = r.n_cand > kCap ? 1 : 0;
             rows[row] = r;
+            s_found = 1;
         }
         before_m += bm[i];
         before_c += bc[i];
+    }
+    __syncthreads();
+    if (tid == 0 && !s_found) {                              // no bin qualifies (a row of NaN): the single kernel's business
+        TruncRow r = {};
+        r.fallback = 1;
+        rows[row] = r;
     }
 }
 

@@ -153,13 +153,14 @@ def test_workspace_path_large_batch_crowded_rows_and_errors(sb):
     logits[6] = np.where(rng.random(V) < 0.5, 0.5, -0.5)        # two values
     logits[7] = (rng.normal(size=V) * 1e-3).astype(np.float32)  # 20000 scores inside a few bins
     logits[129] = 3.0
+    logits[8, ::17] = -np.inf                                   # masked-out tokens
     ids = np.arange(B, dtype=np.int32); steps = np.arange(B, dtype=np.int32)
     for T, k, p in ((0.6, 0, 0.95), (1.0, 40, 1.0), (0.8, 9000, 0.9), (1.0, 12000, 1.0)):
         p32 = float(np.float32(p))
         a = _run(sb, logits, T, k, p32, 3, ids, steps)
         b = _run(sb, logits, T, k, p32, 3, ids, steps, ws=True)
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1]), (T, k, p)
-        for r in (0, 5, 6, 7, 127, 128, 129, 130):
+        for r in (0, 5, 6, 7, 8, 127, 128, 129, 130):
             g = osamp.gumbel_noise(3, r, int(steps[r]), V)
             tok, margin, tau, slack = otr.sample_row(logits[r], T, k, p32, g)
             if slack >= SLACK:
