@@ -9,10 +9,12 @@
 // c + 2 are issued.  Every wave owns a 128 x 128 quarter: per k step of 16 it reads 4 + 4 operand
 // fragments from LDS (one step ahead of their use) for 16 v_mfma_f32_32x32x16 (256 accumulator
 // registers), i.e. 128 flop per byte fetched from L2 against 64 for a 128 x 128 tile; the issue order of
-// a step is pinned (8 LDS reads, then 4 x (4 MFMAs, 1 LDS write)) so that LDS traffic runs under the
-// MFMAs.  An isolated inner loop of this shape reaches 73 % of the MFMA peak (one MFMA per 39 cycles
-// back to back, 45 B/clk of LDS operand reads beside them); the kernel 0.67-0.98 PFLOP/s at 8192 rows, where 320 tiles of the two
-// narrow projections fill 256 CUs 1.25 times (the vendor GEMM: 1.0-1.4 PFLOP/s on these shapes).
+// a step is pinned (8 LDS reads, then 4 x (4 MFMAs, 1 LDS write, 1 global load)) so that LDS and memory
+// traffic run under the MFMAs: issued as one burst at the start of a chunk the 16 loads of a thread cost a
+// sixth of the kernel, spread over the k steps nothing measurable.  An isolated loop of this shape runs at 71 %
+// of the nominal MFMA rate (a pure MFMA stream at 82 %: the clock under this load is ~2.0 GHz); the kernel delivers
+// 1.0-1.15 PFLOP/s on 16,384 rows, the matrix cores busy 52-57 % of the cycles at 1.9-2.0 GHz (the vendor GEMM:
+// 1.0-1.4 PFLOP/s on these shapes).
 // Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the tile order is arranged so
 // that each XCD (own L2) gets a contiguous run of tiles, ordered in bands of 4 row tiles.
 #include "spiral_internal.h"
@@ -142,10 +144,8 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs 
             for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[j][i] = mma32t(wf[ks & 1][j], af[ks & 1][i], acc[j][i]);
-#ifndef TILE_SCHED
-#define TILE_SCHED 1
-#endif
-#if TILE_SCHED == 1
+            // issue order of the step: the 8 operand reads of the next step, then four groups of 4 MFMAs, one LDS write
+            // and one global load (other orders of the same instructions measured within noise of this one)
             if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -153,33 +153,6 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs 
                 __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
-#elif TILE_SCHED == 2
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-#elif TILE_SCHED == 3
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            }
-#elif TILE_SCHED == 4
-            if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-                __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
-            }
-#endif
             __builtin_amdgcn_sched_barrier(0);
         }
     };
