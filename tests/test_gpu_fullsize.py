@@ -185,6 +185,14 @@ def test_c4_context_of_five_thousand_tokens(progress):
     assert compared > 0
 
 
+def test_c5_context_at_the_end_of_the_run(progress):
+    """The 7B shape (no q/k norm, QKV bias, 7 query heads per kv head) on its longest history at run-end length,
+    2048 + 1024 tokens: the case with the least margin under the logit bar on short histories."""
+    _PROGRESS[0] = progress
+    worst, compared = _run("C5", n_check=1, decode_steps=2, pick="longest", extend=1024, check_steps=[0, 2])
+    assert compared > 0
+
+
 def test_c3_full_batch_is_deterministic_and_position_in_batch_does_not_matter(progress):
     """Properties that need no oracle, at the benchmark's size and launch configuration: two runs give the
     same bits, and a sequence whose history is repeated elsewhere in the batch gets the same logits there
