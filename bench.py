@@ -41,7 +41,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_session(wl, total_new_tokens, prefill_group_tokens, tune=None):
+def build_session(wl, total_new_tokens, prefill_group_tokens, tune=None, weight_std=0.02):
     import torch
     from paper_2506_24119_amd import binding as sb
     from paper_2506_24119_amd import inputs as si
@@ -50,9 +50,9 @@ def build_session(wl, total_new_tokens, prefill_group_tokens, tune=None):
     dev = "cuda:0"
     t0 = time.time()
     if g.n_layers * g.params_per_layer() > 50_000_000:
-        w = si.make_weights_torch(g, wl.seed, dev)
+        w = si.make_weights_torch(g, wl.seed, dev, std=weight_std)
     else:
-        w = sb.weights_to_device(si.make_weights(g, wl.seed), dev)
+        w = sb.weights_to_device(si.make_weights(g, wl.seed, std=weight_std), dev)
     torch.cuda.synchronize()
     log(f"[bench] weights ready in {time.time() - t0:.1f}s")
     prompts = si.make_prompts(g.vocab, wl.batch, wl.prompt_lo, wl.prompt_hi, wl.seed)
@@ -256,6 +256,10 @@ def main():
     ap.add_argument("--unfused", action="store_true", help="spiral_decode_step + spiral_sample instead of the fused step")
     ap.add_argument("--tune", default=None, help="spiral_model_tune spec (launch decompositions; measurement only)")
     ap.add_argument("--prefill-group-tokens", type=int, default=16384)
+    ap.add_argument("--weight-std", type=float, default=0.02,
+                    help="standard deviation of the random-init matrices (the recipe's is 0.02).  0 makes every operand "
+                         "zero: a diagnostic of how far the matrix cores' power limit, which depends on the operand "
+                         "bits, sets the large-M GEMM times; its line is marked and is not a result")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the scoring-pass and truncated-sampler measurements")
@@ -290,7 +294,7 @@ def main():
     fused = (not args.unfused) and g.weight_dtype == 1 and g.d_model % 128 == 0 and g.vocab % 16 == 0
     # the timed window [P, P + K) of the run; the W warm-up steps are the ones just before it
     P = max(W, (run_len - K) // 2) if (args.window == "centered" and K < run_len) else W
-    sess, prompts, lens0 = build_session(wl, P + K, args.prefill_group_tokens, tune=args.tune)
+    sess, prompts, lens0 = build_session(wl, P + K, args.prefill_group_tokens, tune=args.tune, weight_std=args.weight_std)
     ids = np.arange(B, dtype=np.int32)
     seed = 1000 + wl.seed
 
@@ -372,7 +376,7 @@ def main():
         "ms_per_step": 1e3 * dt / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 (bf16 weights widened in registers; f16 activations and KV cache; f32 accumulate)"
                  if "f16 MFMA" in sb.spiral_version() else "bf16",
-        "data": "synthetic",
+        "data": "synthetic" if args.weight_std == 0.02 else f"synthetic, DIAGNOSTIC weight std {args.weight_std} (not the workload's recipe)",
         "config": {"workload": f"{wl.key}: {g.name}-shaped random init, batch {B}, prompts U[{wl.prompt_lo},{wl.prompt_hi}], "
                                f"{run_len} decode steps, T={wl.temperature} seeded Gumbel-max sampling, 16-token pages; timed: {window}",
                    "timed_window": [P, P + K], "run_steps": run_len, "repeats": R, "repeat_seconds": times,

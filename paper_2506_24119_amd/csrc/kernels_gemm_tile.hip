@@ -6,7 +6,8 @@
 // are conflict free; the weights come from the fragment-ordered copies, 1 KB contiguous per wave
 // load, already in the operand type).  Three chunks are in flight: chunk c is multiplied out of one
 // LDS buffer, chunk c + 1 moves from registers into the other buffer, and the global loads of chunk
-// c + 2 are issued.  Every wave owns a 128 x 128 quarter: per k step of 16 it reads 4 + 4 operand
+// c + 2 are issued; the one barrier of a chunk sits before its last k step, so that the first operand reads of the
+// next chunk are issued under MFMAs like all the others.  Every wave owns a 128 x 128 quarter: per k step of 16 it reads 4 + 4 operand
 // fragments from LDS (one step ahead of their use) for 16 v_mfma_f32_32x32x16 (256 accumulator
 // registers), i.e. 128 flop per byte fetched from L2 against 64 for a 128 x 128 tile; the issue order of
 // a step is pinned (8 LDS reads, then 4 x (4 MFMAs, 1 LDS write, 1 global load)) so that LDS and memory
@@ -14,7 +15,8 @@
 // sixth of the kernel, spread over the k steps nothing measurable.  An isolated loop of this shape runs at 71 %
 // of the nominal MFMA rate (a pure MFMA stream at 82 %: the clock under this load is ~2.0 GHz); the kernel delivers
 // 1.0-1.15 PFLOP/s on 16,384 rows, the matrix cores busy 52-57 % of the cycles at 1.9-2.0 GHz (the vendor GEMM:
-// 1.0-1.4 PFLOP/s on these shapes).
+// 0.9-1.4 PFLOP/s on these shapes).  The clock follows the operand bits: with all-zero operands the gate/up
+// projection takes 1.09 ms instead of 1.41 (1.50 PFLOP/s; the vendor GEMM 1.3-1.4 -> 1.9-2.0 PFLOP/s).
 // Workgroup ids are dealt round-robin to the 8 XCDs by the hardware; the tile order is arranged so
 // that each XCD (own L2) gets a contiguous run of tiles, ordered in bands of 4 row tiles.
 #include "spiral_internal.h"
@@ -122,31 +124,42 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs 
 #pragma unroll
         for (int j = 0; j < J; ++j) wf[j] = *(const u32x4*)(buf + w_frag + j * 32 * ROW + ks * 32);
     };
-    // Chunk c sits in LDS buffer c & 1; chunk c + 1 sits in register stage `nx`; stage `cu` is free.
-    // Per k step: the operand fragments of the next step are read from LDS, four units of chunk c + 1
-    // are parked in the other buffer (its readers finished before the last barrier), and the issue order
-    // is pinned to 8 reads, then 4 x (4 MFMAs, 1 write), so that LDS traffic runs under the MFMAs.
+    // Chunk c sits in LDS buffer c & 1 and came through register stage c & 1.  The barrier of a chunk sits before
+    // its last k step, not after it: by then every wave has issued (and waited for) its last operand reads of the
+    // chunk and has parked all of chunk c + 1, so the last k step already reads the first fragments of chunk c + 1
+    // and starts parking chunk c + 2 into the buffer that just became free - no operand read is ever exposed
+    // behind a barrier.  Per k step: the 8 operand reads of the next step, four units parked, four units requested
+    // (each unit is requested four k steps before it is parked), 16 MFMAs; issue order pinned to 8 reads, then
+    // 4 x (4 MFMAs, 1 write, 1 global load) (other orders of the same instructions measured within noise).
+    u32x4 af[2][4], wf[2][J];
     auto chunk = [&](int c, const int cu, const int nx) {
-        const char* buf = lds + (c & 1) * STAGE;
-        char* other = lds + ((c + 1) & 1) * STAGE;
-        u32x4 af[2][4], wf[2][J];
-        frags(buf, 0, af[0], wf[0]);
-        const int cc = c + 2 < NC ? c + 2 : NC - 1;   // past the end: a re-read of the last chunk
+        char* buf = lds + cu * STAGE;                 // cu == c & 1
+        char* other = lds + nx * STAGE;
+        const int c2 = c + 2 < NC ? c + 2 : NC - 1;   // past the end: a re-read of the last chunk
+        const int c3 = c + 3 < NC ? c + 3 : NC - 1;
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            if (ks < 3) frags(buf, ks + 1, af[(ks + 1) & 1], wf[(ks + 1) & 1]);
+            if (ks < 3) {
+                frags(buf, ks + 1, af[(ks + 1) & 1], wf[(ks + 1) & 1]);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) park_unit(other, nx, ks * 4 + u);
+                for (int u = 0; u < 4; ++u) park_unit(other, nx, (ks + 1) * 4 + u);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) load_unit(cu, cc, ks * 4 + u);
+                for (int u = 0; u < 4; ++u) load_unit(cu, c2, (ks + 1) * 4 + u);
+            } else {
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                frags(other, 0, af[0], wf[0]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) park_unit(buf, cu, u);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) load_unit(nx, c3, u);
+            }
 #pragma unroll
             for (int j = 0; j < J; ++j)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) acc[j][i] = mma32t(wf[ks & 1][j], af[ks & 1][i], acc[j][i]);
-            // issue order of the step: the 8 operand reads of the next step, then four groups of 4 MFMAs, one LDS write
-            // and one global load (other orders of the same instructions measured within noise of this one)
-            if (ks < 3) __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
@@ -161,18 +174,19 @@ __global__ __launch_bounds__(256) void gemm_tile_kernel(GemmArgs g, QkvPostArgs 
     load(1, 1);
 #pragma unroll
     for (int u = 0; u < 16; ++u) park_unit(lds, 0, u);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) park_unit(lds + STAGE, 1, u);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) load_unit(0, 2 < NC ? 2 : NC - 1, u);
     __syncthreads();
+    frags(lds, 0, af[0], wf[0]);
     int c = 0;
     for (; c + 2 <= NC; c += 2) {
         chunk(c, 0, 1);
-        __syncthreads();
         chunk(c + 1, 1, 0);
-        __syncthreads();
     }
-    if (c < NC) {
-        chunk(c, 0, 1);
-        __syncthreads();
-    }
+    if (c < NC) chunk(c, 0, 1);
+    __syncthreads();                                  // the operand buffers are free for the epilogue
 
     // ---- epilogue.  In a 32 x 32 tile a lane holds batch row l32 and, in registers 4b..4b+3, weight rows 8b + 4*lh .. +3:
     //      written straight from there a store instruction touches 64 rows x 16 (or 8) bytes.  Each wave therefore
